@@ -1,0 +1,243 @@
+/*
+ * hfreshard — train <-> generation weight resharding of the HybridFlow
+ * 3D-HybridEngine (arXiv 2409.19256, Section 5) on one MI355X (gfx950).
+ *
+ * All simulated ranks live in two device buffers of one process:
+ *   train_buf : the N = p*t*d training shards (Megatron layout, fused QKV and
+ *               fused gate/up), rank regions concatenated in rank order;
+ *   gen_buf   : the generation partitions (separate q/k/v/gate/up) of the
+ *               "materialised" ranks, concatenated in the order they were given.
+ * The paper's all-gather inside each micro-DP group (Section 5.2 step 1,
+ * Section 5.4) becomes a list of strided copy descriptors executed by one HIP
+ * kernel; the re-partition for training (Section 5.2 step 4) is the inverse list.
+ *
+ * Conventions
+ *   - plain C ABI, no exceptions cross it; every function that can fail returns
+ *     0 (HF_OK) or a negative hf_status; hf_last_error() gives a thread-local text.
+ *   - "device pointer" = memory of the HIP device that was current when the plan
+ *     was built; "host pointer" = ordinary process memory.
+ *   - sizes and offsets are in BYTES unless a name says otherwise; weights are
+ *     opaque 16-bit words (bf16), row-major [out, in].
+ *   - byte layout of a rank region (both buffers): tensors in table order, each
+ *     start rounded up to 256 B, region size rounded up to 4096 B.
+ *     training order : embed (first stage) | per layer ln1 qkv o ln2 gate_up down |
+ *                      lnf head (last stage)
+ *     generation order: embed (first gen stage) | per layer ln1 q k v o ln2 gate up
+ *                      down | lnf head (last gen stage)
+ *     fused qkv [(n_q+2 n_kv)/t*hd, h]: per local KV group: its n_q/n_kv query
+ *     heads, then its key head, then its value head.  fused gate_up [2F/t, h]: the
+ *     rank's gate rows, then its up rows.
+ */
+#ifndef HFRESHARD_H
+#define HFRESHARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(HF_BUILD)
+#define HF_API __attribute__((visibility("default")))
+#else
+#define HF_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HF_OK = 0,
+  HF_EINVAL = -1, /* null pointer, non-positive size, elem_bytes != 2, tied embedding,
+                     misaligned buffer, wrong direction, plan without device copy   */
+  HF_EDIVIS = -2, /* t%t_g, p%p_g, L%p, L%p_g, V%t, F%t, n_q%n_kv, n_kv%t or n_kv%t_g != 0 */
+  HF_ERANGE = -3, /* rank out of range or listed twice; index past the end; a size that
+                     does not fit the descriptor fields                              */
+  HF_ENOMEM = -4, /* host or device allocation failed while building the plan        */
+  HF_EHIP = -5    /* HIP runtime error (no device, launch failure)                   */
+} hf_status;
+
+/* Model shape: a Llama-style decoder (RMSNorm vectors, GQA attention, SwiGLU MLP,
+ * untied embedding / LM head).  The paper evaluates Llama 7B-70B (Section 8.1). */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t elem_bytes; /* must be 2 */
+  int32_t tied_embed; /* must be 0 */
+} hf_model_desc;
+
+/* Training 3D-parallel sizes p-t-d (Section 5.1).  Rank r = dp*p*t + pp*t + tp:
+ * TP and PP groups are consecutive ranks, DP groups are at stride p*t (Section 5.3). */
+typedef struct {
+  int32_t pp, tp, dp;
+} hf_train_layout;
+
+/* hf_gen_layout.flags */
+#define HF_SKIP_OWN 0x0u         /* default: a rank's own pieces are resident in its
+                                    generation buffer and are never copied (Section 5.3,
+                                    zero redundancy; Section 5.4: only remote parameters
+                                    are collected)                                       */
+#define HF_COPY_OWN 0x1u         /* execute also copies the own pieces                  */
+#define HF_GROUPING_VANILLA 0x2u /* HybridFlow-V grouping (Section 5.3, Figure 8(a)):
+                                    consecutive ranks form generation TP/PP groups      */
+#define HF_PLAN_HOST_ONLY 0x4u   /* build no device copy of the plan: every query works,
+                                    execute/back/install return HF_EINVAL.  For hosts
+                                    without a GPU.                                      */
+
+/* Generation sizes p_g-t_g (Section 5.1); the micro-DP size is derived,
+ * d_g = p*t/(p_g*t_g).  mat_ranks (host pointer, copied) lists the ranks whose
+ * generation buffer exists in gen_buf, in buffer order; NULL means all N ranks. */
+typedef struct {
+  int32_t pp, tp;
+  uint32_t flags;
+  const int32_t *mat_ranks;
+  int32_t n_mat;
+} hf_gen_layout;
+
+typedef struct hf_plan hf_plan; /* opaque; owned by the library */
+
+/* tensor ids (hf_desc.tensor_id is the id on the GENERATION side) */
+enum {
+  HF_T_EMBED = 0, HF_T_LN1, HF_T_QKV, HF_T_O, HF_T_LN2, HF_T_GATE_UP, HF_T_DOWN, HF_T_LNF, HF_T_HEAD,
+  HF_G_EMBED = 16, HF_G_LN1, HF_G_Q, HF_G_K, HF_G_V, HF_G_O, HF_G_LN2, HF_G_GATE, HF_G_UP, HF_G_DOWN,
+  HF_G_LNF, HF_G_HEAD
+};
+
+/* hf_desc.kind */
+enum {
+  HF_COL = 0,          /* column-parallel: concatenate along dim 0 (embed, head)       */
+  HF_ROW = 1,          /* row-parallel: concatenate along dim 1 (o, down)              */
+  HF_REPL = 2,         /* replicated vector (norms)                                    */
+  HF_QKV_DEINT = 3,    /* fused qkv <-> separate q / k / v                              */
+  HF_GATEUP_DEINT = 4  /* fused gate_up <-> separate gate / up                          */
+};
+
+/* hf_desc.flags */
+#define HF_DESC_OWN 0x1u     /* source rank == destination rank                         */
+#define HF_DESC_ALIGN16 0x10u /* widest vector that divides every offset, stride, size  */
+#define HF_DESC_ALIGN8 0x20u
+#define HF_DESC_ALIGN4 0x40u
+#define HF_DESC_ALIGN2 0x80u
+
+/* One strided copy: n_blocks x rows x row_bytes.
+ * byte (b, r, i) of the source, at src_off + b*src_block_stride + r*src_row_stride + i,
+ * goes to dst_off + b*dst_block_stride + r*dst_row_stride + i.  For the direction
+ * train->gen src_off is relative to train_buf and dst_off to gen_buf; for gen->train
+ * the other way round. */
+typedef struct {
+  int32_t src_rank, dst_rank, tensor_id, layer; /* layer = -1 for embed / lnf / head */
+  uint32_t kind, flags;
+  uint64_t src_off, dst_off;
+  uint32_t n_blocks, rows, row_bytes, _pad;
+  uint64_t src_block_stride, dst_block_stride, src_row_stride, dst_row_stride;
+} hf_desc;
+
+/* One tensor of one rank region. */
+typedef struct {
+  int32_t tensor_id, layer;
+  uint32_t rows, cols;   /* elements */
+  uint64_t offset;       /* bytes from the base of train_buf / gen_buf */
+  int32_t tp_index;      /* TP index of the slice (training) or generation TP index;
+                            0 for replicated tensors */
+  int32_t replicated;    /* 1 for norm vectors */
+} hf_tensor_info;
+
+/* One unit of device work (what a workgroup copies at a time): rows x row_bytes with
+ * byte strides; produced from the descriptors by the planner's tiler. */
+typedef struct {
+  uint64_t src_off, dst_off;
+  uint32_t rows, row_bytes;
+  uint32_t src_row_stride, dst_row_stride;
+  uint32_t vec_bytes;    /* 16, 8, 4 or 2: widest access that is aligned everywhere */
+  uint32_t _pad;
+} hf_tile;
+
+#define HF_DIR_TRAIN_TO_GEN 0
+#define HF_DIR_GEN_TO_TRAIN 1
+#define HF_BUF_TRAIN 0
+#define HF_BUF_GEN 1
+
+/* ---- plan -------------------------------------------------------------------
+ * hf_reshard_plan: host work only plus one upload of the tile lists to the current
+ * HIP device (unless HF_PLAN_HOST_ONLY).  Builds rank coordinates (Section 5.3),
+ * tensor tables, and the copy descriptors of step 1 and step 4 (Section 5.2).  All
+ * argument structs are host pointers and are copied.  *out receives the plan; the
+ * caller releases it with hf_plan_destroy (which frees the device copy). */
+HF_API int hf_reshard_plan(const hf_model_desc *model, const hf_train_layout *train, const hf_gen_layout *gen,
+                    hf_plan **out);
+HF_API void hf_plan_destroy(hf_plan *plan);
+
+/* ---- execution ----------------------------------------------------------------
+ * train_buf / gen_buf: DEVICE pointers, 256-byte aligned, at least
+ * hf_plan_train_bytes / hf_plan_gen_bytes long, not overlapping; they may be two
+ * offsets into one allocation.  hip_stream: a hipStream_t (NULL = default stream).
+ * The calls enqueue one kernel launch on that stream and return; they never allocate,
+ * synchronise or touch host copies of the buffers.  Padding between tensors is never
+ * written.
+ *
+ * hf_reshard_execute (Section 5.2 step 1; Section 5.4): fills the generation buffers
+ *   of the materialised ranks from the training shards of their micro-DP groups.
+ *   Under HF_SKIP_OWN the own pieces are left alone (they must already be resident,
+ *   see hf_reshard_install_own); under HF_COPY_OWN they are copied too.
+ * hf_reshard_back (Section 5.2 step 4): rewrites the training shard of every
+ *   materialised rank from that rank's own generation buffer.  HF_EINVAL for a plan
+ *   with HF_GROUPING_VANILLA, where the training shard is not inside the generation
+ *   buffer (Section 5.3) and has to be kept besides it instead.
+ * hf_reshard_install_own: copies only the own pieces train_buf[r] -> gen_buf[r]; the
+ *   one-time placement that makes HF_SKIP_OWN's residency assumption true. */
+HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
+HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
+HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
+
+/* ---- tuning (host; takes effect on the next launch) -----------------------------
+ * HF_PARAM_TILE_BYTES re-tiles and re-uploads (allocates; not for the hot path). */
+enum {
+  HF_PARAM_TILE_BYTES = 0,   /* bytes of work per tile, 4096 .. 4 MiB, multiple of 4096   */
+  HF_PARAM_GRID_WGS = 1,     /* workgroups of the persistent kernel, 1 .. 65536           */
+  HF_PARAM_VARIANT = 2       /* HF_VARIANT_*                                              */
+};
+enum {
+  HF_VARIANT_PERSISTENT = 0, /* persistent workgroups stride over the tile list, direct
+                                global->register->global 16-byte accesses               */
+  HF_VARIANT_ONE_WG_PER_TILE = 1, /* same copy loop, one workgroup per tile             */
+  HF_VARIANT_LDS_STAGED = 2  /* persistent, tile staged through LDS                     */
+};
+HF_API int hf_plan_set_param(hf_plan *plan, int param, int64_t value);
+HF_API int64_t hf_plan_get_param(const hf_plan *plan, int param);
+
+/* ---- queries (host only, no device work) --------------------------------------- */
+HF_API size_t hf_plan_train_bytes(const hf_plan *plan);              /* required size of train_buf */
+HF_API size_t hf_plan_gen_bytes(const hf_plan *plan);                /* required size of gen_buf   */
+HF_API int hf_plan_num_ranks(const hf_plan *plan);                   /* N = p*t*d                  */
+HF_API int hf_plan_num_mat(const hf_plan *plan);
+HF_API int hf_plan_mat_rank(const hf_plan *plan, int i);             /* i-th materialised rank, -1 */
+HF_API size_t hf_plan_rank_train_offset(const hf_plan *plan, int rank); /* (size_t)-1 on bad rank  */
+HF_API size_t hf_plan_rank_gen_offset(const hf_plan *plan, int rank);   /* (size_t)-1 if not mat.  */
+/* out[6] = dp, pp, tp, gpp, gtp, micro-DP index (Section 5.3) */
+HF_API int hf_plan_rank_coords(const hf_plan *plan, int rank, int32_t out[6]);
+HF_API int hf_plan_micro_dp_size(const hf_plan *plan);               /* d_g (Section 5.1)          */
+HF_API size_t hf_plan_num_tensors(const hf_plan *plan, int which_buf, int rank);
+HF_API int hf_plan_get_tensor(const hf_plan *plan, int which_buf, int rank, size_t i, hf_tensor_info *out);
+/* copy descriptors that execute (direction 0) / back (direction 1) perform */
+HF_API size_t hf_plan_num_desc(const hf_plan *plan, int direction);
+HF_API int hf_plan_get_desc(const hf_plan *plan, int direction, size_t i, hf_desc *out);
+HF_API size_t hf_plan_bytes_moved(const hf_plan *plan, int direction); /* sum n_blocks*rows*row_bytes */
+/* bytes of distinct source addresses those descriptors read (a training shard read by
+ * several generation ranks counts once) */
+HF_API size_t hf_plan_unique_src_bytes(const hf_plan *plan, int direction);
+/* own view: where the pieces of rank's own training shard sit in its generation
+ * buffer (src_off in train_buf, dst_off in gen_buf); the zero-redundancy overlap */
+HF_API size_t hf_plan_num_own_view(const hf_plan *plan, int rank);
+HF_API int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out);
+/* device work list of a direction, in launch order (for host-side checking) */
+HF_API size_t hf_plan_num_tiles(const hf_plan *plan, int direction);
+HF_API int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out);
+/* full consistency check of the plan on the host: destinations pairwise disjoint and
+ * inside tensor payloads, sources inside tensor payloads, tiles cover the descriptors
+ * exactly.  O(bytes/row) time: meant for tests, not for the hot path. */
+HF_API int hf_plan_validate(const hf_plan *plan);
+
+HF_API const char *hf_last_error(void);
+HF_API const char *hf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HFRESHARD_H */

@@ -556,3 +556,15 @@ class ReshardOracle:
             "hybridflow_v": {"comm": (t * p - 1) / (t * p) * M, "peak": M, "redundancy": M / (t * p)},
             "hybridflow": {"comm": (t * p - tg * pg) / (tg * pg * t * p) * M, "peak": M / (tg * pg), "redundancy": 0.0},
         }
+
+    def full_coords_of_gen(self, r: int, kind: str, lrow: int, lcol: int) -> Tuple[str, int, int]:
+        """(full tensor name, row, col) of element (lrow, lcol) of rank r's generation
+        tensor `kind`: the slice rule of the generation partition read backwards."""
+        _, gtp, _ = self.gen_coords(r)
+        name = self._GEN_TO_FULL[kind]
+        rows, cols = self._gen_shape(kind)
+        if name in REPLICATED:
+            return name, 0, lcol
+        if name in ("wo", "wd"):
+            return name, lrow, gtp * cols + lcol
+        return name, gtp * rows + lrow, lcol

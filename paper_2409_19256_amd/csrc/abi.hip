@@ -1,0 +1,319 @@
+// C ABI of libhfreshard (declarations and contracts: include/hfreshard.h).
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "hfreshard.h"
+#include "kernels.hpp"
+#include "plan.hpp"
+
+// the Python binding mirrors these layouts field by field
+static_assert(sizeof(hf_desc) == 88 && sizeof(hf_tile) == 40 && sizeof(hf_tensor_info) == 32, "ABI struct layout");
+static_assert(sizeof(hf_model_desc) == 36 && sizeof(hf_gen_layout) == 32 && sizeof(hf_train_layout) == 12, "ABI struct layout");
+
+struct hf_plan {
+  hf::Plan p;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &msg) {
+  g_err = msg;
+  return code;
+}
+
+void free_device(hf::Plan &p) {
+  if (p.d_tiles_fwd) (void)hipFree(p.d_tiles_fwd);
+  if (p.d_tiles_back) (void)hipFree(p.d_tiles_back);
+  p.d_tiles_fwd = p.d_tiles_back = nullptr;
+}
+
+int upload_list(const std::vector<hf_tile> &v, hf_tile **out) {
+  *out = nullptr;
+  if (v.empty()) return HF_OK;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(out), v.size() * sizeof(hf_tile));
+  if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? HF_ENOMEM : HF_EHIP, std::string("hipMalloc: ") + hipGetErrorString(e));
+  e = hipMemcpy(*out, v.data(), v.size() * sizeof(hf_tile), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail(HF_EHIP, std::string("hipMemcpy: ") + hipGetErrorString(e));
+  return HF_OK;
+}
+
+int upload(hf::Plan &p) {
+  free_device(p);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(HF_EHIP, std::string("no HIP device: ") + hipGetErrorString(e));
+  p.device = dev;
+  int rc = upload_list(p.tiles_fwd, &p.d_tiles_fwd);
+  if (rc == HF_OK) rc = upload_list(p.tiles_back, &p.d_tiles_back);
+  if (rc != HF_OK) free_device(p);
+  return rc;
+}
+
+int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) {
+  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
+  if (plan->p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
+  if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
+    return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
+  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
+  if (t0 < g0 + plan->p.gen_bytes && g0 < t0 + plan->p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
+  return HF_OK;
+}
+
+int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const void *src, void *dst, void *stream) {
+  const int e = hf::launch_tiles(tiles, n, src, dst, (int)p.variant, (int)p.grid_wgs, stream);
+  if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
+  return HF_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int hf_reshard_plan(const hf_model_desc *model, const hf_train_layout *train, const hf_gen_layout *gen, hf_plan **out) {
+  if (out) *out = nullptr;
+  if (!model || !train || !gen || !out) return fail(HF_EINVAL, "null argument");
+  hf_plan *pl = new (std::nothrow) hf_plan();
+  if (!pl) return fail(HF_ENOMEM, "out of host memory");
+  std::string err;
+  int rc;
+  try {
+    rc = hf::build_plan(*model, *train, *gen, pl->p, err);
+  } catch (const std::bad_alloc &) {
+    rc = HF_ENOMEM;
+    err = "out of host memory while building the plan";
+  }
+  if (rc == HF_OK && !(gen->flags & HF_PLAN_HOST_ONLY)) {
+    rc = upload(pl->p);
+    if (rc != HF_OK) err = g_err;
+  }
+  if (rc != HF_OK) {
+    delete pl;
+    return fail(rc, err);
+  }
+  *out = pl;
+  return HF_OK;
+}
+
+void hf_plan_destroy(hf_plan *plan) {
+  if (!plan) return;
+  free_device(plan->p);
+  delete plan;
+}
+
+int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
+  if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
+  const hf::Plan &p = plan->p;
+  const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
+  return launch(p, p.d_tiles_fwd, n, train_buf, gen_buf, hip_stream);
+}
+
+int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
+  if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
+  const hf::Plan &p = plan->p;
+  return launch(p, p.d_tiles_fwd + p.n_tiles_fwd_peer, p.tiles_fwd.size() - p.n_tiles_fwd_peer, train_buf, gen_buf, hip_stream);
+}
+
+int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream) {
+  if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
+  const hf::Plan &p = plan->p;
+  if (p.flags & HF_GROUPING_VANILLA)
+    return fail(HF_EINVAL, "vanilla grouping keeps the training shard besides the generation buffer: nothing to re-partition");
+  return launch(p, p.d_tiles_back, p.tiles_back.size(), gen_buf, train_buf, hip_stream);
+}
+
+int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
+  if (!plan) return fail(HF_EINVAL, "null plan");
+  hf::Plan &p = plan->p;
+  switch (param) {
+  case HF_PARAM_TILE_BYTES: {
+    const int64_t old = p.tile_bytes;
+    p.tile_bytes = value;
+    std::string err;
+    int rc;
+    try {
+      rc = hf::build_tiles(p, err);
+    } catch (const std::bad_alloc &) {
+      rc = HF_ENOMEM;
+      err = "out of host memory while tiling";
+    }
+    if (rc != HF_OK) {
+      p.tile_bytes = old;
+      std::string e2;
+      (void)hf::build_tiles(p, e2);
+      return fail(rc, err);
+    }
+    if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload(p);
+    return HF_OK;
+  }
+  case HF_PARAM_GRID_WGS:
+    if (value < 1 || value > 65536) return fail(HF_EINVAL, "grid workgroups must be in [1, 65536]");
+    p.grid_wgs = value;
+    return HF_OK;
+  case HF_PARAM_VARIANT:
+    if (value < HF_VARIANT_PERSISTENT || value > HF_VARIANT_LDS_STAGED) return fail(HF_EINVAL, "unknown kernel variant");
+    p.variant = value;
+    return HF_OK;
+  }
+  return fail(HF_EINVAL, "unknown parameter");
+}
+
+int64_t hf_plan_get_param(const hf_plan *plan, int param) {
+  if (!plan) return -1;
+  switch (param) {
+  case HF_PARAM_TILE_BYTES: return plan->p.tile_bytes;
+  case HF_PARAM_GRID_WGS: return plan->p.grid_wgs;
+  case HF_PARAM_VARIANT: return plan->p.variant;
+  }
+  return -1;
+}
+
+size_t hf_plan_train_bytes(const hf_plan *plan) { return plan ? plan->p.train_bytes : 0; }
+size_t hf_plan_gen_bytes(const hf_plan *plan) { return plan ? plan->p.gen_bytes : 0; }
+int hf_plan_num_ranks(const hf_plan *plan) { return plan ? plan->p.N : 0; }
+int hf_plan_num_mat(const hf_plan *plan) { return plan ? (int)plan->p.mat.size() : 0; }
+int hf_plan_mat_rank(const hf_plan *plan, int i) {
+  return (plan && i >= 0 && i < (int)plan->p.mat.size()) ? plan->p.mat[i] : -1;
+}
+int hf_plan_micro_dp_size(const hf_plan *plan) { return plan ? plan->p.dg : 0; }
+
+size_t hf_plan_rank_train_offset(const hf_plan *plan, int rank) {
+  if (!plan || rank < 0 || rank >= plan->p.N) return (size_t)-1;
+  return plan->p.train_tab[rank].base;
+}
+
+size_t hf_plan_rank_gen_offset(const hf_plan *plan, int rank) {
+  if (!plan || rank < 0 || rank >= plan->p.N || plan->p.mat_pos[rank] < 0) return (size_t)-1;
+  return plan->p.gen_tab[rank].base;
+}
+
+int hf_plan_rank_coords(const hf_plan *plan, int rank, int32_t out[6]) {
+  if (!plan || !out) return fail(HF_EINVAL, "null argument");
+  if (rank < 0 || rank >= plan->p.N) return fail(HF_ERANGE, "rank out of range");
+  const hf::Coords &c = plan->p.coords[rank];
+  out[0] = c.dp; out[1] = c.pp; out[2] = c.tp; out[3] = c.gpp; out[4] = c.gtp; out[5] = c.micro;
+  return HF_OK;
+}
+
+size_t hf_plan_num_tensors(const hf_plan *plan, int which_buf, int rank) {
+  if (!plan || rank < 0 || rank >= plan->p.N) return 0;
+  if (which_buf == HF_BUF_TRAIN) return plan->p.train_tab[rank].tensors.size();
+  if (which_buf == HF_BUF_GEN && plan->p.mat_pos[rank] >= 0) return plan->p.gen_tab[rank].tensors.size();
+  return 0;
+}
+
+int hf_plan_get_tensor(const hf_plan *plan, int which_buf, int rank, size_t i, hf_tensor_info *out) {
+  if (!plan || !out) return fail(HF_EINVAL, "null argument");
+  if (which_buf != HF_BUF_TRAIN && which_buf != HF_BUF_GEN) return fail(HF_EINVAL, "which_buf must be HF_BUF_TRAIN or HF_BUF_GEN");
+  if (rank < 0 || rank >= plan->p.N) return fail(HF_ERANGE, "rank out of range");
+  if (which_buf == HF_BUF_GEN && plan->p.mat_pos[rank] < 0) return fail(HF_ERANGE, "rank has no generation buffer");
+  const hf::RankTable &tab = which_buf == HF_BUF_TRAIN ? plan->p.train_tab[rank] : plan->p.gen_tab[rank];
+  if (i >= tab.tensors.size()) return fail(HF_ERANGE, "tensor index past the end");
+  const hf::TensorRec &t = tab.tensors[i];
+  const hf::Coords &c = plan->p.coords[rank];
+  const bool repl = t.id == HF_T_LN1 || t.id == HF_T_LN2 || t.id == HF_T_LNF || t.id == HF_G_LN1 || t.id == HF_G_LN2 || t.id == HF_G_LNF;
+  out->tensor_id = t.id;
+  out->layer = t.layer;
+  out->rows = t.rows;
+  out->cols = t.cols;
+  out->offset = tab.base + t.off;
+  out->tp_index = repl ? 0 : (which_buf == HF_BUF_TRAIN ? c.tp : c.gtp);
+  out->replicated = repl ? 1 : 0;
+  return HF_OK;
+}
+
+static const hf_desc *desc_at(const hf::Plan &p, int direction, size_t i) {
+  if (direction == HF_DIR_TRAIN_TO_GEN) {
+    if (i < p.fwd_peer.size()) return &p.fwd_peer[i];
+    i -= p.fwd_peer.size();
+    if ((p.flags & HF_COPY_OWN) && i < p.fwd_own.size()) return &p.fwd_own[i];
+    return nullptr;
+  }
+  if (direction == HF_DIR_GEN_TO_TRAIN && i < p.back.size()) return &p.back[i];
+  return nullptr;
+}
+
+size_t hf_plan_num_desc(const hf_plan *plan, int direction) {
+  if (!plan) return 0;
+  const hf::Plan &p = plan->p;
+  if (direction == HF_DIR_TRAIN_TO_GEN) return p.fwd_peer.size() + ((p.flags & HF_COPY_OWN) ? p.fwd_own.size() : 0);
+  if (direction == HF_DIR_GEN_TO_TRAIN) return p.back.size();
+  return 0;
+}
+
+int hf_plan_get_desc(const hf_plan *plan, int direction, size_t i, hf_desc *out) {
+  if (!plan || !out) return fail(HF_EINVAL, "null argument");
+  const hf_desc *d = desc_at(plan->p, direction, i);
+  if (!d) return fail(HF_ERANGE, "no such descriptor");
+  *out = *d;
+  return HF_OK;
+}
+
+size_t hf_plan_bytes_moved(const hf_plan *plan, int direction) {
+  if (!plan) return 0;
+  size_t total = 0;
+  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) total += hf::desc_bytes(*desc_at(plan->p, direction, i));
+  return total;
+}
+
+size_t hf_plan_unique_src_bytes(const hf_plan *plan, int direction) {
+  if (!plan) return 0;
+  std::vector<const hf_desc *> v;
+  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) v.push_back(desc_at(plan->p, direction, i));
+  return hf::unique_src_bytes(v);
+}
+
+size_t hf_plan_num_own_view(const hf_plan *plan, int rank) {
+  if (!plan || rank < 0 || rank >= plan->p.N) return 0;
+  size_t n = 0;
+  for (const hf_desc &d : plan->p.fwd_own) n += d.dst_rank == rank;
+  return n;
+}
+
+int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out) {
+  if (!plan || !out) return fail(HF_EINVAL, "null argument");
+  if (rank < 0 || rank >= plan->p.N) return fail(HF_ERANGE, "rank out of range");
+  for (const hf_desc &d : plan->p.fwd_own)
+    if (d.dst_rank == rank && i-- == 0) {
+      *out = d;
+      return HF_OK;
+    }
+  return fail(HF_ERANGE, "no such own-view entry");
+}
+
+size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
+  if (!plan) return 0;
+  const hf::Plan &p = plan->p;
+  if (direction == HF_DIR_TRAIN_TO_GEN) return (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
+  if (direction == HF_DIR_GEN_TO_TRAIN) return p.tiles_back.size();
+  return 0;
+}
+
+int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out) {
+  if (!plan || !out) return fail(HF_EINVAL, "null argument");
+  if (i >= hf_plan_num_tiles(plan, direction)) return fail(HF_ERANGE, "no such tile");
+  *out = direction == HF_DIR_TRAIN_TO_GEN ? plan->p.tiles_fwd[i] : plan->p.tiles_back[i];
+  return HF_OK;
+}
+
+int hf_plan_validate(const hf_plan *plan) {
+  if (!plan) return fail(HF_EINVAL, "null plan");
+  std::string err;
+  int rc;
+  try {
+    rc = hf::validate_plan(plan->p, err);
+  } catch (const std::bad_alloc &) {
+    rc = HF_ENOMEM;
+    err = "out of host memory while validating";
+  }
+  return rc == HF_OK ? HF_OK : fail(rc, err);
+}
+
+const char *hf_last_error(void) { return g_err.c_str(); }
+const char *hf_version(void) { return "hfreshard 0.1 (gfx950)"; }
+
+} // extern "C"

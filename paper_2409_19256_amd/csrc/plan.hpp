@@ -1,0 +1,76 @@
+// Internal representation of a reshard plan (host side).  Not part of the ABI.
+#pragma once
+
+#include <cstdint>
+#include <map>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "hfreshard.h"
+
+namespace hf {
+
+// Position of a rank in the training grid and in the generation grid
+// (HybridFlow Section 5.1 for the sizes, Section 5.3 for the grouping rules).
+struct Coords {
+  int dp, pp, tp;      // training: r = dp*p*t + pp*t + tp
+  int gpp, gtp, micro; // generation stage, generation TP index, index in the micro-DP group
+};
+
+struct TensorRec {
+  int id;        // HF_T_* or HF_G_*
+  int layer;     // global layer, -1 for embed / lnf / head
+  uint32_t rows, cols;
+  uint64_t off;  // bytes from the start of the rank region
+};
+
+struct RankTable {
+  std::vector<TensorRec> tensors;
+  std::map<std::pair<int, int>, int> index; // (id, layer) -> position in `tensors`
+  uint64_t size = 0;                        // region bytes (multiple of 4096)
+  uint64_t base = 0;                        // bytes from the buffer base
+  const TensorRec &at(int id, int layer) const { return tensors[index.at({id, layer})]; }
+};
+
+struct Plan {
+  hf_model_desc m{};
+  int p = 0, t = 0, d = 0, pg = 0, tg = 0;
+  uint32_t flags = 0;
+  int a = 0, b = 0, dg = 0, N = 0;
+  int lps = 0, lpgs = 0; // layers per training / generation stage
+  std::vector<int> mat;     // materialised ranks in buffer order
+  std::vector<int> mat_pos; // rank -> position in `mat`, -1 if absent
+  std::vector<Coords> coords;
+  std::vector<RankTable> train_tab, gen_tab; // per rank (gen_tab[r].base valid only if materialised)
+  uint64_t train_bytes = 0, gen_bytes = 0;
+
+  // step 1 (train -> gen): pieces from micro-DP peers, and pieces from the rank's own shard
+  std::vector<hf_desc> fwd_peer, fwd_own;
+  // step 4 (gen -> train): inverse of the own pieces
+  std::vector<hf_desc> back;
+
+  // device work lists; tiles_fwd = [peer tiles | own tiles]
+  std::vector<hf_tile> tiles_fwd, tiles_back;
+  size_t n_tiles_fwd_peer = 0;
+
+  int64_t tile_bytes = 128 * 1024;
+  int64_t grid_wgs = 2048;
+  int64_t variant = HF_VARIANT_PERSISTENT;
+
+  // device copy (null for HF_PLAN_HOST_ONLY)
+  int device = -1;
+  hf_tile *d_tiles_fwd = nullptr;
+  hf_tile *d_tiles_back = nullptr;
+};
+
+// Builds everything except the device copy.  Returns HF_OK or an error, with `err` set.
+int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_layout &gl, Plan &out, std::string &err);
+// (Re)creates the tile lists from the descriptors with out.tile_bytes.
+int build_tiles(Plan &pl, std::string &err);
+// Host-side consistency check (see hf_plan_validate).
+int validate_plan(const Plan &pl, std::string &err);
+uint64_t desc_bytes(const hf_desc &d);
+uint64_t unique_src_bytes(const std::vector<const hf_desc *> &descs);
+
+} // namespace hf

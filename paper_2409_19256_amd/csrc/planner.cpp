@@ -1,0 +1,498 @@
+// Host planner: rank coordinates, tensor tables, copy descriptors and tiles for the
+// train <-> generation weight reshard of the HybridFlow 3D-HybridEngine.
+//
+// Paper passages implemented here (arXiv 2409.19256):
+//   Section 5.1  sizes: N = p*t*d = p_g*t_g*d_g*d, d_g = p*t/(p_g*t_g)
+//   Section 5.3  grouping: training TP/PP groups are consecutive ranks and DP groups sit
+//                at stride p*t; HybridFlow generation TP/PP groups take ranks at stride
+//                t/t_g and p/p_g and micro-DP groups are consecutive ranks; the vanilla
+//                variant reuses the training rule with the smaller sizes
+//   Section 5.2  step 1 = gather of the updated parameters inside each micro-DP group,
+//                step 4 = re-partition for training
+//   Section 5.4  only the remote parameters of the micro-DP group are collected; the own
+//                training shard is reused in place (zero redundancy)
+// Pure host code: no HIP calls in this file.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+#include <set>
+#include <tuple>
+
+namespace hf {
+
+namespace {
+
+constexpr uint64_t kTensorAlign = 256;
+constexpr uint64_t kRankAlign = 4096;
+
+uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+const int kTrainLayerIds[] = {HF_T_LN1, HF_T_QKV, HF_T_O, HF_T_LN2, HF_T_GATE_UP, HF_T_DOWN};
+const int kGenLayerIds[] = {HF_G_LN1, HF_G_Q, HF_G_K, HF_G_V, HF_G_O, HF_G_LN2, HF_G_GATE, HF_G_UP, HF_G_DOWN};
+
+// [rows, cols] of a training-shard tensor (Megatron layout, TP size t)
+void train_shape(const hf_model_desc &m, int t, int id, uint32_t &rows, uint32_t &cols) {
+  const uint32_t h = m.hidden, hd = m.head_dim;
+  switch (id) {
+  case HF_T_EMBED: case HF_T_HEAD: rows = m.vocab / t; cols = h; break;
+  case HF_T_LN1: case HF_T_LN2: case HF_T_LNF: rows = 1; cols = h; break;
+  case HF_T_QKV: rows = (uint32_t)(m.n_q_heads + 2 * m.n_kv_heads) / t * hd; cols = h; break;
+  case HF_T_O: rows = h; cols = (uint32_t)m.n_q_heads * hd / t; break;
+  case HF_T_GATE_UP: rows = 2u * m.ffn / t; cols = h; break;
+  case HF_T_DOWN: rows = h; cols = (uint32_t)m.ffn / t; break;
+  default: rows = cols = 0;
+  }
+}
+
+// [rows, cols] of a generation-buffer tensor (separate q/k/v/gate/up, TP size tg)
+void gen_shape(const hf_model_desc &m, int tg, int id, uint32_t &rows, uint32_t &cols) {
+  const uint32_t h = m.hidden, hd = m.head_dim;
+  switch (id) {
+  case HF_G_EMBED: case HF_G_HEAD: rows = m.vocab / tg; cols = h; break;
+  case HF_G_LN1: case HF_G_LN2: case HF_G_LNF: rows = 1; cols = h; break;
+  case HF_G_Q: rows = (uint32_t)m.n_q_heads * hd / tg; cols = h; break;
+  case HF_G_K: case HF_G_V: rows = (uint32_t)m.n_kv_heads * hd / tg; cols = h; break;
+  case HF_G_O: rows = h; cols = (uint32_t)m.n_q_heads * hd / tg; break;
+  case HF_G_GATE: case HF_G_UP: rows = (uint32_t)m.ffn / tg; cols = h; break;
+  case HF_G_DOWN: rows = h; cols = (uint32_t)m.ffn / tg; break;
+  default: rows = cols = 0;
+  }
+}
+
+template <typename ShapeFn>
+void lay_out(RankTable &tab, bool first, bool last, int layer0, int n_layers, const int *layer_ids, int n_ids,
+             int id_embed, int id_lnf, int id_head, ShapeFn shape) {
+  uint64_t off = 0;
+  auto put = [&](int id, int layer) {
+    TensorRec r;
+    r.id = id;
+    r.layer = layer;
+    shape(id, r.rows, r.cols);
+    off = round_up(off, kTensorAlign);
+    r.off = off;
+    off += (uint64_t)r.rows * r.cols * 2;
+    tab.index[{id, layer}] = (int)tab.tensors.size();
+    tab.tensors.push_back(r);
+  };
+  if (first) put(id_embed, -1);
+  for (int l = layer0; l < layer0 + n_layers; ++l)
+    for (int k = 0; k < n_ids; ++k) put(layer_ids[k], l);
+  if (last) {
+    put(id_lnf, -1);
+    put(id_head, -1);
+  }
+  tab.size = round_up(off, kRankAlign);
+}
+
+uint32_t align_flag(uint64_t x) {
+  if (x % 16 == 0) return HF_DESC_ALIGN16;
+  if (x % 8 == 0) return HF_DESC_ALIGN8;
+  if (x % 4 == 0) return HF_DESC_ALIGN4;
+  return HF_DESC_ALIGN2;
+}
+
+// widest vector that divides every offset, size and (used) stride of the descriptor
+uint32_t desc_align(const hf_desc &d) {
+  uint64_t g = d.src_off | d.dst_off | d.row_bytes;
+  if (d.rows > 1) g |= d.src_row_stride | d.dst_row_stride;
+  if (d.n_blocks > 1) g |= d.src_block_stride | d.dst_block_stride;
+  return align_flag(g); // low set bit of the OR = gcd with a power of two
+}
+
+struct Emitter {
+  Plan &pl;
+  int dst_rank;
+  // offsets are relative to the START OF THE TENSOR on either side
+  void add(int src_rank, const TensorRec &src_t, const TensorRec &dst_t, uint32_t kind, uint64_t src_delta,
+           uint64_t dst_delta, uint32_t n_blocks, uint32_t rows, uint32_t row_bytes, uint64_t sbs, uint64_t dbs,
+           uint64_t srs, uint64_t drs) {
+    hf_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.src_rank = src_rank;
+    d.dst_rank = dst_rank;
+    d.tensor_id = dst_t.id;
+    d.layer = dst_t.layer;
+    d.kind = kind;
+    d.src_off = pl.train_tab[src_rank].base + src_t.off + src_delta;
+    d.dst_off = pl.gen_tab[dst_rank].base + dst_t.off + dst_delta;
+    d.n_blocks = n_blocks;
+    d.rows = rows;
+    d.row_bytes = row_bytes;
+    d.src_block_stride = sbs;
+    d.dst_block_stride = dbs;
+    d.src_row_stride = srs;
+    d.dst_row_stride = drs;
+    d.flags = desc_align(d) | (src_rank == dst_rank ? HF_DESC_OWN : 0u);
+    (src_rank == dst_rank ? pl.fwd_own : pl.fwd_peer).push_back(d);
+  }
+};
+
+} // namespace
+
+uint64_t desc_bytes(const hf_desc &d) { return (uint64_t)d.n_blocks * d.rows * d.row_bytes; }
+
+uint64_t unique_src_bytes(const std::vector<const hf_desc *> &descs) {
+  // pieces read by several destinations are byte-identical descriptors on the source
+  // side; different pieces never overlap (checked by validate_plan through coverage)
+  std::set<std::tuple<uint64_t, uint64_t, uint32_t, uint32_t, uint32_t>> seen;
+  uint64_t total = 0;
+  for (const hf_desc *d : descs)
+    if (seen.insert({d->src_off, d->src_block_stride, d->n_blocks, d->rows, d->row_bytes}).second)
+      total += desc_bytes(*d);
+  return total;
+}
+
+int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_layout &gl, Plan &pl, std::string &err) {
+  // ---- validation -------------------------------------------------------------
+  const int32_t sizes[] = {m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
+                           tl.pp, tl.tp, tl.dp, gl.pp, gl.tp};
+  for (int32_t v : sizes)
+    if (v <= 0) { err = "all model and layout sizes must be positive"; return HF_EINVAL; }
+  if (m.elem_bytes != 2) { err = "elem_bytes must be 2 (bf16)"; return HF_EINVAL; }
+  if (m.tied_embed != 0) { err = "tied embedding / LM head is not supported"; return HF_EINVAL; }
+  if (gl.flags & ~(HF_COPY_OWN | HF_GROUPING_VANILLA | HF_PLAN_HOST_ONLY)) { err = "unknown flag bits"; return HF_EINVAL; }
+  if (gl.mat_ranks && gl.n_mat <= 0) { err = "mat_ranks given but n_mat <= 0"; return HF_EINVAL; }
+  struct { bool bad; const char *what; } div[] = {
+      {tl.tp % gl.tp != 0, "t % t_g"}, {tl.pp % gl.pp != 0, "p % p_g"}, {m.n_layers % tl.pp != 0, "L % p"},
+      {m.n_layers % gl.pp != 0, "L % p_g"}, {m.vocab % tl.tp != 0, "V % t"}, {m.ffn % tl.tp != 0, "F % t"},
+      {m.n_q_heads % m.n_kv_heads != 0, "n_q % n_kv"}, {m.n_kv_heads % tl.tp != 0, "n_kv % t"},
+      {m.n_kv_heads % gl.tp != 0, "n_kv % t_g"}};
+  for (auto &c : div)
+    if (c.bad) { err = std::string("not divisible: ") + c.what; return HF_EDIVIS; }
+  const int64_t n64 = (int64_t)tl.pp * tl.tp * tl.dp;
+  if (n64 > (1 << 20)) { err = "too many ranks"; return HF_ERANGE; }
+  // row lengths and block strides must fit 32-bit fields of descriptors and tiles
+  const uint64_t widest_row = 2ull * std::max<uint64_t>(m.hidden, std::max<uint64_t>(m.ffn, (uint64_t)m.n_q_heads * m.head_dim));
+  const uint64_t qkv_group = 2ull * ((uint64_t)m.n_q_heads / m.n_kv_heads + 2) * m.head_dim * m.hidden;
+  if (widest_row >= (1ull << 31) || qkv_group >= (1ull << 32)) { err = "tensor rows too long for 32-bit strides"; return HF_ERANGE; }
+
+  pl.m = m;
+  pl.p = tl.pp; pl.t = tl.tp; pl.d = tl.dp; pl.pg = gl.pp; pl.tg = gl.tp;
+  pl.flags = gl.flags;
+  pl.a = pl.t / pl.tg;
+  pl.b = pl.p / pl.pg;
+  pl.dg = pl.a * pl.b;
+  pl.N = (int)n64;
+  pl.lps = m.n_layers / pl.p;
+  pl.lpgs = m.n_layers / pl.pg;
+  const int N = pl.N, p = pl.p, t = pl.t, pg = pl.pg, tg = pl.tg, a = pl.a, b = pl.b;
+  const bool vanilla = (gl.flags & HF_GROUPING_VANILLA) != 0;
+
+  // ---- materialised ranks ------------------------------------------------------
+  pl.mat_pos.assign(N, -1);
+  if (gl.mat_ranks) {
+    for (int i = 0; i < gl.n_mat; ++i) {
+      const int r = gl.mat_ranks[i];
+      if (r < 0 || r >= N) { err = "materialised rank out of range"; return HF_ERANGE; }
+      if (pl.mat_pos[r] >= 0) { err = "materialised rank listed twice"; return HF_ERANGE; }
+      pl.mat_pos[r] = i;
+      pl.mat.push_back(r);
+    }
+  } else {
+    for (int r = 0; r < N; ++r) { pl.mat_pos[r] = r; pl.mat.push_back(r); }
+  }
+
+  // ---- rank coordinates ----------------------------------------------------------
+  pl.coords.resize(N);
+  for (int r = 0; r < N; ++r) {
+    Coords &c = pl.coords[r];
+    c.dp = r / (p * t);
+    c.pp = (r % (p * t)) / t;
+    c.tp = r % t;
+    if (!vanilla) {
+      // generation TP peers are t/t_g training ranks apart and generation PP peers p/p_g
+      // stages apart: quotient = generation index, remainder = place in the micro-DP group
+      c.gtp = c.tp / a;
+      c.gpp = c.pp / b;
+      c.micro = (c.pp % b) * a + (c.tp % a);
+    } else {
+      const int i = c.pp * t + c.tp; // place inside the replica; consecutive ranks per group
+      c.gtp = i % tg;
+      c.gpp = (i / tg) % pg;
+      c.micro = i / (tg * pg);
+    }
+  }
+
+  // ---- tensor tables -----------------------------------------------------------
+  pl.train_tab.assign(N, RankTable());
+  pl.gen_tab.assign(N, RankTable());
+  uint64_t base = 0;
+  for (int r = 0; r < N; ++r) {
+    const Coords &c = pl.coords[r];
+    lay_out(pl.train_tab[r], c.pp == 0, c.pp == p - 1, c.pp * pl.lps, pl.lps, kTrainLayerIds, 6, HF_T_EMBED, HF_T_LNF,
+            HF_T_HEAD, [&](int id, uint32_t &rows, uint32_t &cols) { train_shape(m, t, id, rows, cols); });
+    pl.train_tab[r].base = base;
+    base += pl.train_tab[r].size;
+    lay_out(pl.gen_tab[r], c.gpp == 0, c.gpp == pg - 1, c.gpp * pl.lpgs, pl.lpgs, kGenLayerIds, 9, HF_G_EMBED, HF_G_LNF,
+            HF_G_HEAD, [&](int id, uint32_t &rows, uint32_t &cols) { gen_shape(m, tg, id, rows, cols); });
+  }
+  pl.train_bytes = base;
+  base = 0;
+  for (int r : pl.mat) {
+    pl.gen_tab[r].base = base;
+    base += pl.gen_tab[r].size;
+  }
+  pl.gen_bytes = base;
+
+  // ---- step 1 descriptors: for every materialised rank, every generation tensor, every
+  // training shard that contributes to it ------------------------------------------
+  const uint64_t h2 = 2ull * m.hidden;                 // bytes of one [*, h] row
+  const uint32_t hd = m.head_dim, qpg = m.n_q_heads / m.n_kv_heads;
+  const uint32_t ng = m.n_kv_heads / t;                // KV groups per training shard
+  const uint64_t grp = (uint64_t)(qpg + 2) * hd * h2;  // bytes of one fused [q..q k v] group
+  for (int r : pl.mat) {
+    const Coords &c = pl.coords[r];
+    Emitter em{pl, r};
+    auto rank_of = [&](int pp, int tp) { return c.dp * p * t + pp * t + tp; };
+    for (const TensorRec &g : pl.gen_tab[r].tensors) {
+      // training stage that owns the tensor
+      const int spp = g.id == HF_G_EMBED ? 0 : (g.id == HF_G_LNF || g.id == HF_G_HEAD) ? p - 1 : g.layer / pl.lps;
+      if (g.id == HF_G_LN1 || g.id == HF_G_LN2 || g.id == HF_G_LNF) {
+        // replicated: take the copy of the rank with the same TP index in the owning stage
+        const int q = rank_of(spp, c.tp);
+        const int tid = g.id == HF_G_LN1 ? HF_T_LN1 : g.id == HF_G_LN2 ? HF_T_LN2 : HF_T_LNF;
+        em.add(q, pl.train_tab[q].at(tid, g.layer), g, HF_REPL, 0, 0, 1, 1, (uint32_t)h2, h2, h2, h2, h2);
+        continue;
+      }
+      for (int k = 0; k < a; ++k) {                    // the a training TP shards inside generation shard gtp
+        const int q = rank_of(spp, c.gtp * a + k);
+        const RankTable &st = pl.train_tab[q];
+        switch (g.id) {
+        case HF_G_EMBED: case HF_G_HEAD: {
+          const TensorRec &s = st.at(g.id == HF_G_EMBED ? HF_T_EMBED : HF_T_HEAD, -1);
+          em.add(q, s, g, HF_COL, 0, (uint64_t)k * s.rows * h2, 1, s.rows, (uint32_t)h2, 0, 0, h2, h2);
+          break;
+        }
+        case HF_G_Q: case HF_G_K: case HF_G_V: {
+          const TensorRec &s = st.at(HF_T_QKV, g.layer);
+          const uint32_t rows = g.id == HF_G_Q ? qpg * hd : hd;             // rows of one group's piece
+          const uint64_t in_group = g.id == HF_G_Q ? 0 : g.id == HF_G_K ? (uint64_t)qpg * hd * h2 : (uint64_t)(qpg + 1) * hd * h2;
+          em.add(q, s, g, HF_QKV_DEINT, in_group, (uint64_t)k * ng * rows * h2, ng, rows, (uint32_t)h2, grp,
+                 (uint64_t)rows * h2, h2, h2);
+          break;
+        }
+        case HF_G_GATE: case HF_G_UP: {
+          const TensorRec &s = st.at(HF_T_GATE_UP, g.layer);
+          const uint32_t rows = s.rows / 2;                                  // F/t
+          em.add(q, s, g, HF_GATEUP_DEINT, g.id == HF_G_GATE ? 0 : (uint64_t)rows * h2, (uint64_t)k * rows * h2, 1, rows,
+                 (uint32_t)h2, 0, 0, h2, h2);
+          break;
+        }
+        case HF_G_O: case HF_G_DOWN: {
+          const TensorRec &s = st.at(g.id == HF_G_O ? HF_T_O : HF_T_DOWN, g.layer);
+          em.add(q, s, g, HF_ROW, 0, (uint64_t)k * s.cols * 2, 1, s.rows, s.cols * 2, 0, 0, (uint64_t)s.cols * 2,
+                 (uint64_t)g.cols * 2);
+          break;
+        }
+        default: err = "internal: unknown generation tensor"; return HF_EINVAL;
+        }
+      }
+    }
+  }
+
+  // ---- step 4 descriptors: the own pieces, run backwards ----------------------------
+  if (!vanilla) {
+    pl.back.reserve(pl.fwd_own.size());
+    for (const hf_desc &o : pl.fwd_own) {
+      hf_desc d = o;
+      std::swap(d.src_off, d.dst_off);
+      std::swap(d.src_block_stride, d.dst_block_stride);
+      std::swap(d.src_row_stride, d.dst_row_stride);
+      pl.back.push_back(d);
+    }
+  }
+  return build_tiles(pl, err);
+}
+
+// ---- tiler --------------------------------------------------------------------------
+namespace {
+
+uint32_t vec_of(uint64_t g) { return g % 16 == 0 ? 16 : g % 8 == 0 ? 8 : g % 4 == 0 ? 4 : 2; }
+
+void push_tile(std::vector<hf_tile> &out, uint64_t src, uint64_t dst, uint32_t rows, uint32_t row_bytes, uint32_t sstr,
+               uint32_t dstr) {
+  hf_tile tl;
+  std::memset(&tl, 0, sizeof tl);
+  tl.src_off = src;
+  tl.dst_off = dst;
+  tl.rows = rows;
+  tl.row_bytes = row_bytes;
+  tl.src_row_stride = rows > 1 ? sstr : row_bytes;
+  tl.dst_row_stride = rows > 1 ? dstr : row_bytes;
+  uint64_t g = src | dst | row_bytes;
+  if (rows > 1) g |= (uint64_t)sstr | dstr;
+  tl.vec_bytes = vec_of(g);
+  out.push_back(tl);
+}
+
+// one contiguous run of `len` bytes -> chunks of about tile_bytes, cut at 256-byte steps
+void tile_run(std::vector<hf_tile> &out, uint64_t src, uint64_t dst, uint64_t len, uint64_t tile_bytes) {
+  const uint64_t n = (len + tile_bytes - 1) / tile_bytes;
+  const uint64_t chunk = round_up((len + n - 1) / n, 256);
+  for (uint64_t o = 0; o < len; o += chunk) push_tile(out, src + o, dst + o, 1, (uint32_t)std::min(chunk, len - o), 0, 0);
+}
+
+void tile_desc(std::vector<hf_tile> &out, const hf_desc &d, uint64_t tile_bytes) {
+  const bool rows_contig = d.rows == 1 || (d.src_row_stride == d.row_bytes && d.dst_row_stride == d.row_bytes);
+  const uint64_t block_len = (uint64_t)d.rows * d.row_bytes;
+  const bool blocks_contig = d.n_blocks == 1 || (d.src_block_stride == block_len && d.dst_block_stride == block_len);
+  if (rows_contig && blocks_contig) {
+    tile_run(out, d.src_off, d.dst_off, block_len * d.n_blocks, tile_bytes);
+    return;
+  }
+  for (uint32_t bidx = 0; bidx < d.n_blocks; ++bidx) {
+    const uint64_t s = d.src_off + bidx * d.src_block_stride, t = d.dst_off + bidx * d.dst_block_stride;
+    if (rows_contig) {
+      tile_run(out, s, t, block_len, tile_bytes);
+    } else if (d.row_bytes >= tile_bytes) {
+      for (uint32_t r = 0; r < d.rows; ++r) tile_run(out, s + r * d.src_row_stride, t + r * d.dst_row_stride, d.row_bytes, tile_bytes);
+    } else {
+      // rows per tile: about tile_bytes of payload, and offsets inside a tile below 4 GiB
+      // (the kernel computes row*stride in 32 bits)
+      const uint64_t widest = std::max(d.src_row_stride, d.dst_row_stride);
+      const uint64_t fit = ((1ull << 32) - 1 - d.row_bytes) / std::max<uint64_t>(widest, 1) + 1;
+      const uint32_t per = (uint32_t)std::max<uint64_t>(1, std::min(tile_bytes / d.row_bytes, fit));
+      for (uint32_t r = 0; r < d.rows; r += per)
+        push_tile(out, s + r * d.src_row_stride, t + r * d.dst_row_stride, std::min(per, d.rows - r), d.row_bytes,
+                  (uint32_t)d.src_row_stride, (uint32_t)d.dst_row_stride);
+    }
+  }
+}
+
+} // namespace
+
+int build_tiles(Plan &pl, std::string &err) {
+  if (pl.tile_bytes < 4096 || pl.tile_bytes > (4 << 20) || pl.tile_bytes % 4096) {
+    err = "tile bytes must be a multiple of 4096 in [4096, 4 MiB]";
+    return HF_EINVAL;
+  }
+  pl.tiles_fwd.clear();
+  pl.tiles_back.clear();
+  for (const hf_desc &d : pl.fwd_peer) tile_desc(pl.tiles_fwd, d, (uint64_t)pl.tile_bytes);
+  pl.n_tiles_fwd_peer = pl.tiles_fwd.size();
+  for (const hf_desc &d : pl.fwd_own) tile_desc(pl.tiles_fwd, d, (uint64_t)pl.tile_bytes);
+  for (const hf_desc &d : pl.back) tile_desc(pl.tiles_back, d, (uint64_t)pl.tile_bytes);
+  if (pl.tiles_fwd.size() >= (1ull << 31) || pl.tiles_back.size() >= (1ull << 31)) {
+    err = "too many tiles; raise the tile size";
+    return HF_ERANGE;
+  }
+  return HF_OK;
+}
+
+// ---- validation -------------------------------------------------------------------------
+namespace {
+
+struct Seg { uint64_t dst, src, len; };
+
+void desc_segments(const hf_desc &d, std::vector<Seg> &out) {
+  for (uint32_t b = 0; b < d.n_blocks; ++b)
+    for (uint32_t r = 0; r < d.rows; ++r)
+      out.push_back({d.dst_off + b * d.dst_block_stride + r * d.dst_row_stride,
+                     d.src_off + b * d.src_block_stride + r * d.src_row_stride, d.row_bytes});
+}
+
+void tile_segments(const hf_tile &t, std::vector<Seg> &out) {
+  for (uint32_t r = 0; r < t.rows; ++r)
+    out.push_back({t.dst_off + (uint64_t)r * t.dst_row_stride, t.src_off + (uint64_t)r * t.src_row_stride, t.row_bytes});
+}
+
+// sort by destination and merge neighbours that are contiguous on both sides
+bool normalise(std::vector<Seg> &v, std::string &err, const char *what) {
+  std::sort(v.begin(), v.end(), [](const Seg &x, const Seg &y) { return x.dst < y.dst; });
+  std::vector<Seg> m;
+  for (const Seg &s : v) {
+    if (!m.empty()) {
+      Seg &l = m.back();
+      if (l.dst + l.len > s.dst) { err = std::string(what) + ": overlapping destinations"; return false; }
+      if (l.dst + l.len == s.dst && l.src + l.len == s.src) { l.len += s.len; continue; }
+    }
+    m.push_back(s);
+  }
+  v.swap(m);
+  return true;
+}
+
+bool same(const std::vector<Seg> &x, const std::vector<Seg> &y) {
+  if (x.size() != y.size()) return false;
+  for (size_t i = 0; i < x.size(); ++i)
+    if (x[i].dst != y[i].dst || x[i].src != y[i].src || x[i].len != y[i].len) return false;
+  return true;
+}
+
+int train_id_of(int gen_id) {
+  switch (gen_id) {
+  case HF_G_EMBED: return HF_T_EMBED;
+  case HF_G_HEAD: return HF_T_HEAD;
+  case HF_G_LN1: return HF_T_LN1;
+  case HF_G_LN2: return HF_T_LN2;
+  case HF_G_LNF: return HF_T_LNF;
+  case HF_G_Q: case HF_G_K: case HF_G_V: return HF_T_QKV;
+  case HF_G_O: return HF_T_O;
+  case HF_G_GATE: case HF_G_UP: return HF_T_GATE_UP;
+  case HF_G_DOWN: return HF_T_DOWN;
+  }
+  return -1;
+}
+
+} // namespace
+
+int validate_plan(const Plan &pl, std::string &err) {
+  // (1) every descriptor stays inside the payload of the tensors it names
+  auto inside = [&](const hf_desc &d, bool forward) -> bool {
+    const int train_rank = forward ? d.src_rank : d.dst_rank, gen_rank = forward ? d.dst_rank : d.src_rank;
+    const RankTable &tt = pl.train_tab[train_rank], &gt = pl.gen_tab[gen_rank];
+    const TensorRec &tr = tt.at(train_id_of(d.tensor_id), d.layer), &gr = gt.at(d.tensor_id, d.layer);
+    const uint64_t t0 = tt.base + tr.off, t1 = t0 + 2ull * tr.rows * tr.cols;
+    const uint64_t g0 = gt.base + gr.off, g1 = g0 + 2ull * gr.rows * gr.cols;
+    const uint64_t s_lo = d.src_off, s_hi = d.src_off + (d.n_blocks - 1) * d.src_block_stride + (d.rows - 1) * d.src_row_stride + d.row_bytes;
+    const uint64_t d_lo = d.dst_off, d_hi = d.dst_off + (d.n_blocks - 1) * d.dst_block_stride + (d.rows - 1) * d.dst_row_stride + d.row_bytes;
+    if (forward) return s_lo >= t0 && s_hi <= t1 && d_lo >= g0 && d_hi <= g1;
+    return s_lo >= g0 && s_hi <= g1 && d_lo >= t0 && d_hi <= t1;
+  };
+  for (const hf_desc &d : pl.fwd_peer) if (!inside(d, true)) { err = "peer descriptor leaves its tensor"; return HF_ERANGE; }
+  for (const hf_desc &d : pl.fwd_own) if (!inside(d, true)) { err = "own descriptor leaves its tensor"; return HF_ERANGE; }
+  for (const hf_desc &d : pl.back) if (!inside(d, false)) { err = "reverse descriptor leaves its tensor"; return HF_ERANGE; }
+
+  // (2) destinations pairwise disjoint, and together exactly the payload
+  std::vector<Seg> fwd, fwd_peer_only, back;
+  for (const hf_desc &d : pl.fwd_peer) desc_segments(d, fwd);
+  fwd_peer_only = fwd;
+  for (const hf_desc &d : pl.fwd_own) desc_segments(d, fwd);
+  for (const hf_desc &d : pl.back) desc_segments(d, back);
+  uint64_t gen_payload = 0, train_payload = 0, fwd_total = 0, back_total = 0;
+  for (int r : pl.mat) {
+    for (const TensorRec &g : pl.gen_tab[r].tensors) gen_payload += 2ull * g.rows * g.cols;
+    for (const TensorRec &s : pl.train_tab[r].tensors) train_payload += 2ull * s.rows * s.cols;
+  }
+  for (const Seg &s : fwd) fwd_total += s.len;
+  for (const Seg &s : back) back_total += s.len;
+  if (!normalise(fwd, err, "train->gen") || !normalise(back, err, "gen->train")) return HF_ERANGE;
+  if (fwd_total != gen_payload) { err = "train->gen descriptors do not cover the generation payload"; return HF_ERANGE; }
+  if (!(pl.flags & HF_GROUPING_VANILLA) && back_total != train_payload) {
+    err = "gen->train descriptors do not cover the training payload";
+    return HF_ERANGE;
+  }
+
+  // (3) the tiles are exactly the descriptors
+  std::vector<Seg> tf, tf_peer, tb;
+  for (size_t i = 0; i < pl.tiles_fwd.size(); ++i) {
+    tile_segments(pl.tiles_fwd[i], tf);
+    if (i + 1 == pl.n_tiles_fwd_peer) tf_peer = tf;
+  }
+  for (const hf_tile &t : pl.tiles_back) tile_segments(t, tb);
+  if (!normalise(tf, err, "train->gen tiles") || !normalise(tb, err, "gen->train tiles") ||
+      !normalise(tf_peer, err, "peer tiles") || !normalise(fwd_peer_only, err, "peer descriptors"))
+    return HF_ERANGE;
+  if (!same(tf, fwd) || !same(tb, back) || !same(tf_peer, fwd_peer_only)) { err = "tiles differ from descriptors"; return HF_ERANGE; }
+  for (const std::vector<hf_tile> *lst : {&pl.tiles_fwd, &pl.tiles_back})
+    for (const hf_tile &t : *lst) {
+      uint64_t g = t.src_off | t.dst_off | t.row_bytes;
+      if (t.rows > 1) g |= (uint64_t)t.src_row_stride | t.dst_row_stride;
+      if (g % t.vec_bytes || t.row_bytes == 0 || t.rows == 0) { err = "tile alignment wrong"; return HF_ERANGE; }
+    }
+  return HF_OK;
+}
+
+} // namespace hf

@@ -27,3 +27,14 @@ SMALL = [
     dict(name="odd_rows", model=Model(1, 6, 2, 2, 3, 10, 8), train=TrainLayout(1, 2, 1), gen=GenLayout(1, 1)),
     dict(name="same_layout", model=Model(2, 32, 4, 2, 8, 24, 64), train=TrainLayout(2, 2, 1), gen=GenLayout(2, 2)),
 ]
+
+# Medium shapes: tens of MB, several 128 KiB tiles per descriptor with ragged tails,
+# rows that are 16-, 8-, 4- and only 2-byte aligned, GQA, merged pipeline stages.
+MEDIUM = [
+    dict(name="mid_gqa_tp8pp2_tp2", model=Model(4, 512, 16, 8, 32, 2760, 2000), train=TrainLayout(2, 8, 1),
+         gen=GenLayout(1, 2)),
+    dict(name="mid_mha_tp4_tp1", model=Model(3, 768, 12, 12, 64, 2052, 5004), train=TrainLayout(1, 4, 1),
+         gen=GenLayout(1, 1)),
+    dict(name="mid_gqa_tp4pp4_tp2pp2_dp2", model=Model(8, 520, 8, 4, 65, 1404, 1000), train=TrainLayout(4, 4, 2),
+         gen=GenLayout(2, 2)),
+]

@@ -1,0 +1,284 @@
+"""Host logic of the library (no GPU): the C-ABI loads and exports everything the header
+declares; the planner's coordinates, tables, descriptors and tiles reproduce the oracle
+when interpreted on the CPU; error codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.reshard_oracle import GenLayout, Model, TrainLayout
+from paper_2409_19256_amd import Plan, binding as B
+from tests.cases import BASELINE, SMALL
+from tests.libcases import make_plan, model_dict
+from tests.oracle_util import POISON, make_oracle, mat_ranks, seeded_train_buf, source_index_map
+from tests.plan_interp import run_descs, run_tiles
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = B.HF_PLAN_HOST_ONLY
+CASES = SMALL + [BASELINE[0]]
+IDS = [c["name"] for c in CASES]
+CANARY = 0xC0DE
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "hfreshard.h")).read()
+    declared = set(re.findall(r"^HF_API[^;(]*?\b(hf_\w+)\s*\(", header, flags=re.M))
+    assert len(declared) >= 29
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+        assert name in B.SIGNATURES, name
+    assert set(B.SIGNATURES) == declared
+    assert b"gfx950" in B.hf_version()
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert C.sizeof(B.hf_desc) == 88 and C.sizeof(B.hf_tile) == 40 and C.sizeof(B.hf_tensor_info) == 32
+    assert C.sizeof(B.hf_model_desc) == 36 and C.sizeof(B.hf_gen_layout) == 32
+
+
+@pytest.mark.parametrize("case", CASES + BASELINE[1:], ids=IDS + [c["name"] for c in BASELINE[1:]])
+def test_coords_and_tables_match_oracle(case):
+    orc = make_oracle(case)
+    ranks = mat_ranks(case, orc)
+    with make_plan(case, HOST) as pl:
+        assert pl.n_ranks == orc.n_ranks and pl.micro_dp_size == orc.dg and pl.mat_ranks == ranks
+        assert pl.train_bytes == 2 * orc.train_region_offsets()[-1]
+        assert pl.gen_bytes == 2 * orc.gen_region_offsets(ranks)[-1]
+        gb = dict(zip(ranks, orc.gen_region_offsets(ranks)))
+        for r in range(orc.n_ranks):
+            assert pl.rank_coords(r) == orc.train_coords(r) + orc.gen_coords(r)
+            assert pl.rank_train_offset(r) == 2 * orc.train_region_offsets()[r]
+            got = [(B.TENSOR_NAMES[t.tensor_id], t.layer, t.rows, t.cols, t.offset) for t in pl.tensors(B.HF_BUF_TRAIN, r)]
+            want = [(e.kind, e.layer, e.rows, e.cols, 2 * (orc.train_region_offsets()[r] + e.offset)) for e in orc.train_table(r)[0]]
+            assert got == want
+            if r in gb:
+                assert pl.rank_gen_offset(r) == 2 * gb[r]
+                got = [(B.TENSOR_NAMES[t.tensor_id], t.layer, t.rows, t.cols, t.offset) for t in pl.tensors(B.HF_BUF_GEN, r)]
+                want = [(e.kind, e.layer, e.rows, e.cols, 2 * (gb[r] + e.offset)) for e in orc.gen_table(r)[0]]
+                assert got == want
+            else:
+                assert pl.rank_gen_offset(r) == 2 ** 64 - 1 and pl.tensors(B.HF_BUF_GEN, r) == []
+
+
+def _own_mask(orc, ranks):
+    """bool over gen_buf elements: comes from the holding rank's own training shard."""
+    src = source_index_map(orc, ranks)
+    offs = orc.train_region_offsets()
+    gb = orc.gen_region_offsets(ranks)
+    own = np.zeros(src.shape, bool)
+    for i, r in enumerate(ranks):
+        reg = src[gb[i]:gb[i + 1]]
+        own[gb[i]:gb[i + 1]] = (reg >= offs[r]) & (reg < offs[r + 1])
+    return own
+
+
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+@pytest.mark.parametrize("use_tiles", [False, True], ids=["descs", "tiles"])
+@pytest.mark.parametrize("tile_bytes", [128 * 1024, 4096])
+def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes):
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 4321)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    own = _own_mask(orc, ranks)
+    run = run_tiles if use_tiles else run_descs
+
+    # COPY_OWN: the whole generation buffer, padding untouched
+    with make_plan(case, HOST | B.HF_COPY_OWN) as pl:
+        pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+        pl.validate()
+        items = pl.tiles(0) if use_tiles else pl.descs(0)
+        got = np.full(want.shape, POISON, np.uint16)
+        run(items, train.view(np.uint8), got.view(np.uint8))
+        assert np.array_equal(got, want)
+        assert pl.bytes_moved(0) == 2 * int((want != POISON).sum() + ((want == POISON) & _payload(orc, ranks)).sum())
+
+    # SKIP_OWN: only remote pieces are written; canaries on own pieces and padding survive
+    with make_plan(case, HOST) as pl:
+        pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+        pl.validate()
+        items = pl.tiles(0) if use_tiles else pl.descs(0)
+        got = np.full(want.shape, CANARY, np.uint16)
+        run(items, train.view(np.uint8), got.view(np.uint8))
+        pay = _payload(orc, ranks)
+        remote = pay & ~own
+        assert np.array_equal(got[remote], want[remote])
+        assert (got[~remote] == CANARY).all()
+        assert pl.bytes_moved(0) == 2 * int(remote.sum())
+        # reverse: poisoned training buffer restored from the (complete) generation buffers
+        items = pl.tiles(1) if use_tiles else pl.descs(1)
+        back = np.full(train.shape, 0xBEEF, np.uint16)
+        run(items, want.view(np.uint8), back.view(np.uint8))
+        tpay = _train_payload(orc)
+        assert np.array_equal(back[tpay], train[tpay]) and (back[~tpay] == 0xBEEF).all()
+        assert pl.bytes_moved(1) == 2 * int(tpay.sum())
+
+
+def _payload(orc, ranks):
+    pay = np.zeros(orc.gen_region_offsets(ranks)[-1], bool)
+    for i, r in enumerate(ranks):
+        for e in orc.gen_table(r)[0]:
+            s = orc.gen_region_offsets(ranks)[i] + e.offset
+            pay[s:s + e.n] = True
+    return pay
+
+
+def _train_payload(orc):
+    pay = np.zeros(orc.train_region_offsets()[-1], bool)
+    for r in range(orc.n_ranks):
+        for e in orc.train_table(r)[0]:
+            s = orc.train_region_offsets()[r] + e.offset
+            pay[s:s + e.n] = True
+    return pay
+
+
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_own_view_is_where_the_oracle_finds_the_own_shard(case):
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    src = source_index_map(orc, ranks)       # gen element -> train element (oracle)
+    # the interpreter moves bytes of 16-bit items: transport the index as two 16-bit halves
+    with make_plan(case, HOST) as pl:
+        offs = orc.train_region_offsets()
+        gb = orc.gen_region_offsets(ranks)
+        lo = (np.arange(offs[-1]) & 0xFFFF).astype(np.uint16)
+        hi = (np.arange(offs[-1]) >> 16).astype(np.uint16)
+        for i, r in enumerate(ranks):
+            got_lo = np.full(src.shape, 0xFFFF, np.uint16)
+            got_hi = np.full(src.shape, 0xFFFF, np.uint16)
+            run_descs(pl.own_view(r), lo.view(np.uint8), got_lo.view(np.uint8))
+            run_descs(pl.own_view(r), hi.view(np.uint8), got_hi.view(np.uint8))
+            reg = src[gb[i]:gb[i + 1]]
+            own = (reg >= offs[r]) & (reg < offs[r + 1])
+            got = (got_hi[gb[i]:gb[i + 1]].astype(np.int64) << 16) | got_lo[gb[i]:gb[i + 1]]
+            assert np.array_equal(got[own], reg[own])
+            # nothing outside the own positions of rank r's region is named by its own view
+            assert (got_lo[gb[i]:gb[i + 1]][~own] == 0xFFFF).all()
+            other = np.ones(src.shape, bool)
+            other[gb[i]:gb[i + 1]] = False
+            assert (got_lo[other] == 0xFFFF).all() and (got_hi[other] == 0xFFFF).all()
+            # every element of the training shard is in the view (zero redundancy)
+            assert int(own.sum()) == sum(e.n for e in orc.train_table(r)[0])
+
+
+def test_vanilla_grouping_plan():
+    case = dict(model=Model(2, 32, 4, 4, 8, 24, 64), train=TrainLayout(1, 4, 2), gen=GenLayout(1, 2, "vanilla"))
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 11)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    with make_plan(case, HOST | B.HF_COPY_OWN) as pl:
+        pl.validate()
+        got = np.full(want.shape, POISON, np.uint16)
+        run_tiles(pl.tiles(0), train.view(np.uint8), got.view(np.uint8))
+        assert np.array_equal(got, want)
+        assert pl.num_desc(1) == 0
+        # G2, G3, G6, G7 reuse nothing but their norm vectors
+        sharded_own = [sum(d.n_blocks * d.rows * d.row_bytes for d in pl.own_view(r) if d.kind != B.HF_REPL) for r in ranks]
+        assert [r for r in ranks if sharded_own[r] == 0] == [1, 2, 5, 6]
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_baseline_config_byte_totals(idx):
+    """Bytes the train->gen step writes, against the closed form of Section 5.4:
+    generation payload minus own shard; (d_g-1)/(tp) of the TP-sharded bytes when p = p_g."""
+    case = BASELINE[idx]
+    orc = make_oracle(case)
+    ranks = mat_ranks(case, orc)
+    with make_plan(case, HOST) as pl:
+        W = pl.bytes_moved(0)
+        gen_payload = sum(2 * e.n for r in ranks for e in orc.gen_table(r)[0])
+        own_payload = sum(2 * e.n for r in ranks for e in orc.train_table(r)[0])
+        assert W == gen_payload - own_payload
+        assert pl.bytes_moved(1) == own_payload
+        if orc.p == orc.pg:
+            Ms = orc.model_bytes() - 2 * orc.m.hidden * (2 * orc.m.n_layers + 1)
+            assert W == len(ranks) * (orc.dg - 1) * Ms // (orc.t * orc.p)
+        if case["name"] == "llama7b":
+            assert round(W / 1e9, 2) == 40.43
+            assert pl.unique_src_bytes(0) * 3 == W        # every shard is read by d_g-1 = 3 peers
+        if case["name"] == "llama13b":
+            assert round(W / 1e9, 1) == 78.1
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_baseline_config_descriptors_against_element_definition(idx):
+    """Sampled bytes of sampled descriptors: destination -> logical element (generation
+    slice rule) -> training location (element definition) must be the descriptor's source."""
+    case = BASELINE[idx]
+    orc = make_oracle(case)
+    ranks = mat_ranks(case, orc)
+    gb = dict(zip(ranks, orc.gen_region_offsets(ranks)))
+    rng = np.random.default_rng(idx)
+    with make_plan(case, HOST | B.HF_COPY_OWN) as pl:
+        n = pl.num_desc(0)
+        d = B.hf_desc()
+        for i in rng.choice(n, size=600, replace=False):
+            B.check(B.hf_plan_get_desc(pl._h, 0, int(i), C.byref(d)), "get_desc")
+            kind = B.TENSOR_NAMES[d.tensor_id]
+            e = orc.gen_entry(d.dst_rank, kind, d.layer)
+            for _ in range(4):
+                b, r, k = rng.integers(d.n_blocks), rng.integers(d.rows), rng.integers(d.row_bytes // 2) * 2
+                dst = d.dst_off + b * d.dst_block_stride + r * d.dst_row_stride + k
+                src = d.src_off + b * d.src_block_stride + r * d.src_row_stride + k
+                local = dst // 2 - gb[d.dst_rank] - e.offset
+                assert 0 <= local < e.n
+                name, frow, fcol = orc.full_coords_of_gen(d.dst_rank, kind, local // e.cols, local % e.cols)
+                locs = orc.where_train(orc.train_coords(d.dst_rank)[0], name, d.layer, frow, fcol)
+                assert (d.src_rank, src // 2) in locs, (kind, d.layer, d.dst_rank, d.src_rank)
+
+
+def test_error_codes():
+    m = dict(n_layers=4, hidden=32, n_q_heads=8, n_kv_heads=4, head_dim=4, ffn=24, vocab=64)
+
+    def code(model=m, train=(1, 4, 1), gen=(1, 2), flags=HOST, mat=None):
+        try:
+            Plan(model, train, gen, flags=flags, mat_ranks=mat).close()
+            return 0
+        except B.HfError as e:
+            assert str(e)
+            return e.code
+
+    assert code() == 0
+    assert code(gen=(1, 3)) == B.HF_EDIVIS
+    assert code(train=(3, 4, 1)) == B.HF_EDIVIS
+    assert code(train=(1, 8, 1), gen=(1, 1)) == B.HF_EDIVIS          # n_kv % t
+    assert code(model=dict(m, n_q_heads=6)) == B.HF_EDIVIS
+    assert code(model=dict(m, vocab=66)) == B.HF_EDIVIS
+    assert code(model=dict(m, hidden=0)) == B.HF_EINVAL
+    assert code(model=dict(m, elem_bytes=4)) == B.HF_EINVAL
+    assert code(model=dict(m, tied_embed=1)) == B.HF_EINVAL
+    assert code(flags=HOST | 0x100) == B.HF_EINVAL
+    assert code(mat=[0, 4]) == B.HF_ERANGE
+    assert code(mat=[1, 1]) == B.HF_ERANGE
+    assert code(mat=[2, 0]) == 0
+    assert B.hf_reshard_plan(None, None, None, None) == B.HF_EINVAL
+    with Plan(m, (1, 4, 1), (1, 2), flags=HOST) as pl:
+        # a host-only plan refuses to launch, whatever the pointers
+        assert B.hf_reshard_execute(pl._h, 256, 1 << 20, None) == B.HF_EINVAL
+        assert b"HOST_ONLY" in B.hf_last_error()
+        assert B.hf_reshard_execute(pl._h, None, 256, None) == B.HF_EINVAL
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_TILE_BYTES, 1000)
+        assert pl.get_param(B.HF_PARAM_TILE_BYTES) == 128 * 1024
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_GRID_WGS, 0)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_VARIANT, 9)
+        d = B.hf_desc()
+        assert B.hf_plan_get_desc(pl._h, 0, 10 ** 9, C.byref(d)) == B.HF_ERANGE
+        t = B.hf_tensor_info()
+        assert B.hf_plan_get_tensor(pl._h, 7, 0, 0, C.byref(t)) == B.HF_EINVAL
+        assert B.hf_plan_get_tensor(pl._h, 0, 99, 0, C.byref(t)) == B.HF_ERANGE
+
+
+def test_without_a_gpu_a_device_plan_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.HfError) as ei:
+        Plan(dict(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, head_dim=8, ffn=24, vocab=64), (1, 4, 1), (1, 2))
+    assert ei.value.code == B.HF_EHIP
