@@ -93,7 +93,13 @@ def main():
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--grid", type=int, default=None)
+    ap.add_argument("--multicast", type=int, default=None, choices=[0, 1, 2])
+    ap.add_argument("--part-bytes", type=int, default=None)
+    ap.add_argument("--mc-block-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-bytes", type=int, default=0,
+                    help="after the timed region, launch the library's plain copy kernel once over this many bytes "
+                         "(a dispatch of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU: all simulated ranks live in one HBM allocation and there is no "
@@ -120,6 +126,12 @@ def main():
         plan.set_param(B.HF_PARAM_GRID_WGS, args.grid)
     if args.variant is not None:
         plan.set_param(B.HF_PARAM_VARIANT, args.variant)
+    if args.multicast is not None:
+        plan.set_param(B.HF_PARAM_MULTICAST, args.multicast)
+    if args.part_bytes:
+        plan.set_param(B.HF_PARAM_PART_BYTES, args.part_bytes)
+    if args.mc_block_bytes:
+        plan.set_param(B.HF_PARAM_MC_BLOCK_BYTES, args.mc_block_bytes)
     ar = Arena(plan)
     ar.gen.zero_()
     ar.fill_train_seeded(config_seed(args.config - 1))
@@ -145,7 +157,17 @@ def main():
     ms_per_step = wall_ms / args.steps
     avg_kernel_ms = sum(kern_ms) / len(kern_ms)
 
-    alg_bytes = 2 * W                                    # every moved byte is read once and written once
+    # algorithmic bytes of one launch: every destination byte is written once; source bytes
+    # are read once per destination, or once in all when the kernel multicasts a training
+    # piece to every rank that wants it (then the smaller, distinct-bytes figure counts)
+    multicast = plan.get_param(B.HF_PARAM_MULTICAST) if args.direction == "fwd" else 0
+    alg_bytes = W + (R if multicast else W)
+    if args.calib_copy_bytes:
+        n = min(args.calib_copy_bytes, ar.gen.numel()) // 16 * 16
+        B.check(B.hf_calib_copy(ar.train_ptr, ar.gen_ptr, min(n, ar.train.numel() * 2 // 16 * 16), ar.stream_handle()), "hf_calib_copy")
+        torch.cuda.synchronize()
+        ar.install_own()   # the calibration copy scribbled over gen_buf; nothing after this reads it
+        torch.cuda.synchronize()
     value = alg_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
     out = {
@@ -157,14 +179,19 @@ def main():
                    "ranks": plan.n_ranks, "materialised_gen_ranks": len(plan.mat_ranks), "micro_dp": plan.micro_dp_size,
                    "bytes_written": W, "unique_bytes_read": R, "arena_bytes": ar.buf.numel() * 2,
                    "tile_bytes": plan.get_param(B.HF_PARAM_TILE_BYTES), "grid_wgs": plan.get_param(B.HF_PARAM_GRID_WGS),
-                   "variant": plan.get_param(B.HF_PARAM_VARIANT), "tiles": plan.num_tiles(direction),
+                   "part_bytes": plan.get_param(B.HF_PARAM_PART_BYTES), "mc_block_bytes": plan.get_param(B.HF_PARAM_MC_BLOCK_BYTES),
+                   "variant": plan.get_param(B.HF_PARAM_VARIANT), "multicast": int(multicast),
+                   "unicast_equivalent_GBps": round(2 * W / (avg_kernel_ms * 1e-3) / 1e9, 1),
+                   "tiles": plan.num_tiles(direction),
                    "descriptors": plan.num_desc(direction)},
         "transition_ms": {"mean": round(avg_kernel_ms, 4), "median": round(kern_ms[len(kern_ms) // 2], 4), "min": round(kern_ms[0], 4)},
         "pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "plan_build_upload_ms": round(plan_ms, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "reshard_persistent", "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel": ["reshard_persistent", "reshard_one_tile", "reshard_persistent_lds", "reshard_wave_persistent",
+                                "reshard_parts"][plan.get_param(B.HF_PARAM_VARIANT)],
+                     "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_kernel_ms": round(avg_kernel_ms, 4)},
     }
     if not args.no_cpu_baseline:

@@ -142,10 +142,15 @@ typedef struct {
 /* One unit of device work (what a workgroup copies at a time): rows x row_bytes with
  * byte strides; produced from the descriptors by the planner's tiler. */
 typedef struct {
-  uint64_t src_off, dst_off;
+  uint64_t src_off, dst_off; /* dst_off: the first destination                          */
   uint32_t rows, row_bytes;
   uint32_t src_row_stride, dst_row_stride;
   uint32_t vec_bytes;    /* 16, 8, 4 or 2: widest access that is aligned everywhere */
+  uint32_t n_dst;        /* >= 1.  Multicast: the source tile is read once and written to
+                            n_dst destinations with the same row stride (one training
+                            piece wanted by several ranks of a micro-DP group)           */
+  uint32_t dst_list;     /* position of destinations 2..n_dst in the plan's list of extra
+                            destination offsets (see hf_plan_get_tile_dst)               */
   uint32_t _pad;
 } hf_tile;
 
@@ -186,18 +191,55 @@ HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *
 HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
 
+/* Plain 16-byte grid-stride copy of `bytes` (multiple of 16) from src to dst (DEVICE
+ * pointers, 16-byte aligned, not overlapping) on hip_stream: a kernel of known traffic,
+ * for calibrating hardware counters and for measuring the copy ceiling of a box.
+ * dst == NULL: only reads src; src == NULL: only writes dst (a constant pattern).  Not
+ * part of the paper's method. */
+HF_API int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 /* ---- tuning (host; takes effect on the next launch) -----------------------------
  * HF_PARAM_TILE_BYTES re-tiles and re-uploads (allocates; not for the hot path). */
 enum {
   HF_PARAM_TILE_BYTES = 0,   /* bytes of work per tile, 4096 .. 4 MiB, multiple of 4096   */
-  HF_PARAM_GRID_WGS = 1,     /* workgroups of the persistent kernel, 1 .. 65536           */
-  HF_PARAM_VARIANT = 2       /* HF_VARIANT_*                                              */
+  HF_PARAM_GRID_WGS = 1,     /* workgroups of the persistent kernels, 1 .. 65536          */
+  HF_PARAM_VARIANT = 2,      /* HF_VARIANT_*                                              */
+  HF_PARAM_MULTICAST = 3,    /* HF_MULTICAST_*: how train->gen serves a training piece that
+                                several ranks of a micro-DP group want.  Same result in
+                                every mode; the modes differ in HBM reads.               */
+  HF_PARAM_CACHE_POLICY = 4, /* -1 (default): chosen by the library (non-temporal loads and
+                                stores; plain loads under HF_MULTICAST_CACHE_BLOCKED);
+                                0: both non-temporal; bit 0: plain loads; bit 1: plain
+                                stores (not for HF_VARIANT_LDS_STAGED)                   */
+  HF_PARAM_PART_BYTES = 5,   /* HF_VARIANT_PARTS: payload bytes per workgroup: 4096, 8192,
+                                16384, 32768, or 0 (default) = 8192 for the cache-blocked
+                                train->gen list and 4096 otherwise                       */
+  HF_PARAM_MC_BLOCK_BYTES = 6, /* HF_MULTICAST_CACHE_BLOCKED: source bytes per block,
+                                1 MiB .. 1 GiB, default 2 MiB (re-tiles and re-uploads)  */
+  HF_PARAM_KIND_MASK = 7     /* profiling aid: bit k set = descriptors of kind k (HF_COL ..
+                                HF_GATEUP_DEINT) are executed and counted by
+                                hf_plan_bytes_moved / hf_plan_unique_src_bytes; default 31
+                                = all.  Any other value makes execute/back INCOMPLETE and
+                                hf_plan_validate fail (re-tiles and re-uploads)          */
+};
+enum {
+  HF_MULTICAST_OFF = 0,       /* one read per destination, destination-major order        */
+  HF_MULTICAST_REGISTERS = 1, /* a workgroup loads a tile once and stores it to every
+                                 destination                                             */
+  HF_MULTICAST_CACHE_BLOCKED = 2 /* default: one destination per workgroup, work ordered so
+                                 that a block of source is copied to destination 1, then
+                                 the same block to destination 2, ...; the re-reads are
+                                 served by L2 instead of HBM                             */
 };
 enum {
   HF_VARIANT_PERSISTENT = 0, /* persistent workgroups stride over the tile list, direct
                                 global->register->global 16-byte accesses               */
   HF_VARIANT_ONE_WG_PER_TILE = 1, /* same copy loop, one workgroup per tile             */
-  HF_VARIANT_LDS_STAGED = 2  /* persistent, tile staged through LDS                     */
+  HF_VARIANT_LDS_STAGED = 2, /* persistent, tile staged through LDS                     */
+  HF_VARIANT_WAVE_PERSISTENT = 3, /* persistent, every WAVEFRONT strides over the tile
+                                list on its own (wavefront-level dispatch)              */
+  HF_VARIANT_PARTS = 4       /* one short-lived workgroup per HF_PARAM_PART_BYTES of every
+                                tile, handed out in order by the hardware dispatcher    */
 };
 HF_API int hf_plan_set_param(hf_plan *plan, int param, int64_t value);
 HF_API int64_t hf_plan_get_param(const hf_plan *plan, int param);
@@ -229,6 +271,8 @@ HF_API int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc
 /* device work list of a direction, in launch order (for host-side checking) */
 HF_API size_t hf_plan_num_tiles(const hf_plan *plan, int direction);
 HF_API int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out);
+/* k-th destination offset (0 <= k < n_dst) of tile i */
+HF_API int hf_plan_get_tile_dst(const hf_plan *plan, int direction, size_t i, uint32_t k, uint64_t *out);
 /* full consistency check of the plan on the host: destinations pairwise disjoint and
  * inside tensor payloads, sources inside tensor payloads, tiles cover the descriptors
  * exactly.  O(bytes/row) time: meant for tests, not for the hot path. */

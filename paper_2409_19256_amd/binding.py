@@ -26,8 +26,9 @@ HF_COL, HF_ROW, HF_REPL, HF_QKV_DEINT, HF_GATEUP_DEINT = range(5)
 HF_DESC_OWN, HF_DESC_ALIGN16, HF_DESC_ALIGN8, HF_DESC_ALIGN4, HF_DESC_ALIGN2 = 0x1, 0x10, 0x20, 0x40, 0x80
 HF_DIR_TRAIN_TO_GEN, HF_DIR_GEN_TO_TRAIN = 0, 1
 HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
-HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT = 0, 1, 2
-HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED = 0, 1, 2
+HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_KIND_MASK = 0, 1, 2, 3, 4, 5, 6, 7
+HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED = 0, 1, 2
+HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED, HF_VARIANT_WAVE_PERSISTENT, HF_VARIANT_PARTS = 0, 1, 2, 3, 4
 
 TENSOR_NAMES = {
     HF_T_EMBED: "embed", HF_T_LN1: "ln1", HF_T_QKV: "qkv", HF_T_O: "o", HF_T_LN2: "ln2", HF_T_GATE_UP: "gate_up",
@@ -67,7 +68,7 @@ class hf_tensor_info(C.Structure):
 class hf_tile(C.Structure):
     _fields_ = [("src_off", C.c_uint64), ("dst_off", C.c_uint64), ("rows", C.c_uint32), ("row_bytes", C.c_uint32),
                 ("src_row_stride", C.c_uint32), ("dst_row_stride", C.c_uint32), ("vec_bytes", C.c_uint32),
-                ("_pad", C.c_uint32)]
+                ("n_dst", C.c_uint32), ("dst_list", C.c_uint32), ("_pad", C.c_uint32)]
 
 
 hf_plan_p = C.c_void_p
@@ -102,6 +103,8 @@ SIGNATURES = {
     "hf_plan_get_own_view": (C.c_int, [_P, C.c_int, C.c_size_t, C.POINTER(hf_desc)]),
     "hf_plan_num_tiles": (C.c_size_t, [_P, C.c_int]),
     "hf_plan_get_tile": (C.c_int, [_P, C.c_int, C.c_size_t, C.POINTER(hf_tile)]),
+    "hf_plan_get_tile_dst": (C.c_int, [_P, C.c_int, C.c_size_t, C.c_uint32, C.POINTER(C.c_uint64)]),
+    "hf_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hf_plan_validate": (C.c_int, [_P]),
     "hf_last_error": (C.c_char_p, []),
     "hf_version": (C.c_char_p, []),

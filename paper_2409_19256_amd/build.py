@@ -10,6 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhfreshard.so")
+BENCH_EXE = os.path.join(PKG, "hfbench")
 SOURCES = ["planner.cpp", "reshard_kernels.hip", "abi.hip"]
 
 
@@ -22,7 +23,7 @@ def hipcc() -> str:
 
 def build_library(verbose: bool = True) -> str:
     """Compile every source for gfx950 and link the shared library; returns its path."""
-    cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden",
+    cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden", "-Wl,-soname,libhfreshard.so",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-DHF_BUILD",
@@ -31,6 +32,14 @@ def build_library(verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True, cwd=ROOT)
     os.replace(LIB + ".tmp", LIB)
+    # hfbench: native driver of the C ABI for rocprofv3 runs (no Python in the traced process)
+    cmd = [hipcc(), "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"),
+           "-x", "hip", os.path.join(CSRC, "hfbench.cpp"), "-x", "none", "-L", PKG, "-lhfreshard", "-Wl,-rpath,$ORIGIN", "-o", BENCH_EXE + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, cwd=ROOT)
+    os.replace(BENCH_EXE + ".tmp", BENCH_EXE)
     return LIB
 
 

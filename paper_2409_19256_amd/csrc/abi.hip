@@ -10,7 +10,7 @@
 #include "plan.hpp"
 
 // the Python binding mirrors these layouts field by field
-static_assert(sizeof(hf_desc) == 88 && sizeof(hf_tile) == 40 && sizeof(hf_tensor_info) == 32, "ABI struct layout");
+static_assert(sizeof(hf_desc) == 88 && sizeof(hf_tile) == 48 && sizeof(hf_tensor_info) == 32, "ABI struct layout");
 static_assert(sizeof(hf_model_desc) == 36 && sizeof(hf_gen_layout) == 32 && sizeof(hf_train_layout) == 12, "ABI struct layout");
 
 struct hf_plan {
@@ -29,15 +29,19 @@ int fail(int code, const std::string &msg) {
 void free_device(hf::Plan &p) {
   if (p.d_tiles_fwd) (void)hipFree(p.d_tiles_fwd);
   if (p.d_tiles_back) (void)hipFree(p.d_tiles_back);
-  p.d_tiles_fwd = p.d_tiles_back = nullptr;
+  if (p.d_tiles_fwd_mc) (void)hipFree(p.d_tiles_fwd_mc);
+  if (p.d_mc_dst) (void)hipFree(p.d_mc_dst);
+  if (p.d_tiles_fwd_cb) (void)hipFree(p.d_tiles_fwd_cb);
+  p.d_tiles_fwd = p.d_tiles_back = p.d_tiles_fwd_mc = p.d_tiles_fwd_cb = nullptr;
+  p.d_mc_dst = nullptr;
 }
 
-int upload_list(const std::vector<hf_tile> &v, hf_tile **out) {
+template <typename T> int upload_list(const std::vector<T> &v, T **out) {
   *out = nullptr;
   if (v.empty()) return HF_OK;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(out), v.size() * sizeof(hf_tile));
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(out), v.size() * sizeof(T));
   if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? HF_ENOMEM : HF_EHIP, std::string("hipMalloc: ") + hipGetErrorString(e));
-  e = hipMemcpy(*out, v.data(), v.size() * sizeof(hf_tile), hipMemcpyHostToDevice);
+  e = hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(HF_EHIP, std::string("hipMemcpy: ") + hipGetErrorString(e));
   return HF_OK;
 }
@@ -50,8 +54,33 @@ int upload(hf::Plan &p) {
   p.device = dev;
   int rc = upload_list(p.tiles_fwd, &p.d_tiles_fwd);
   if (rc == HF_OK) rc = upload_list(p.tiles_back, &p.d_tiles_back);
+  if (rc == HF_OK) rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
+  if (rc == HF_OK) rc = upload_list(p.mc_dst, &p.d_mc_dst);
+  if (rc == HF_OK) rc = upload_list(p.tiles_fwd_cb, &p.d_tiles_fwd_cb);
   if (rc != HF_OK) free_device(p);
   return rc;
+}
+
+// re-tile with a new tile size (and the current multicast block size), then re-upload
+int retile(hf::Plan &p, int64_t tile_bytes) {
+  const int64_t old = p.tile_bytes;
+  p.tile_bytes = tile_bytes;
+  std::string err;
+  int rc;
+  try {
+    rc = hf::build_tiles(p, err);
+  } catch (const std::bad_alloc &) {
+    rc = HF_ENOMEM;
+    err = "out of host memory while tiling";
+  }
+  if (rc != HF_OK) {
+    p.tile_bytes = old;
+    std::string e2;
+    (void)hf::build_tiles(p, e2);
+    return fail(rc, err);
+  }
+  if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload(p);
+  return HF_OK;
 }
 
 int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) {
@@ -64,8 +93,15 @@ int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) 
   return HF_OK;
 }
 
-int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const void *src, void *dst, void *stream) {
-  const int e = hf::launch_tiles(tiles, n, src, dst, (int)p.variant, (int)p.grid_wgs, stream);
+// temporal_loads: the work list counts on re-reads being served by L2
+int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *extra_dst, const void *src, void *dst,
+           void *stream, bool temporal_loads = false) {
+  const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : (temporal_loads ? 1 : 0);
+  // measured on the Llama-7B transition: 8 KiB per workgroup is best when later passes hit
+  // L2, 4 KiB for plain one-to-one copies
+  const uint32_t part = p.part_bytes ? (uint32_t)p.part_bytes : (temporal_loads ? 8192u : 4096u);
+  const int e = hf::launch_tiles(tiles, n, extra_dst, src, dst, (int)p.variant, (int)p.grid_wgs, policy,
+                                 (uint32_t)p.tile_bytes, part, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
@@ -108,14 +144,19 @@ void hf_plan_destroy(hf_plan *plan) {
 int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
+  if (p.multicast == HF_MULTICAST_REGISTERS)
+    return launch(p, p.d_tiles_fwd_mc, p.tiles_fwd_mc.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream);
+  if (p.multicast == HF_MULTICAST_CACHE_BLOCKED)
+    return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, true);
   const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
-  return launch(p, p.d_tiles_fwd, n, train_buf, gen_buf, hip_stream);
+  return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream);
 }
 
 int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
-  return launch(p, p.d_tiles_fwd + p.n_tiles_fwd_peer, p.tiles_fwd.size() - p.n_tiles_fwd_peer, train_buf, gen_buf, hip_stream);
+  return launch(p, p.d_tiles_fwd + p.n_tiles_fwd_peer, p.tiles_fwd.size() - p.n_tiles_fwd_peer, nullptr, train_buf, gen_buf,
+                hip_stream);
 }
 
 int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream) {
@@ -123,40 +164,44 @@ int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, v
   const hf::Plan &p = plan->p;
   if (p.flags & HF_GROUPING_VANILLA)
     return fail(HF_EINVAL, "vanilla grouping keeps the training shard besides the generation buffer: nothing to re-partition");
-  return launch(p, p.d_tiles_back, p.tiles_back.size(), gen_buf, train_buf, hip_stream);
+  return launch(p, p.d_tiles_back, p.tiles_back.size(), nullptr, gen_buf, train_buf, hip_stream);
 }
 
 int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
   if (!plan) return fail(HF_EINVAL, "null plan");
   hf::Plan &p = plan->p;
   switch (param) {
-  case HF_PARAM_TILE_BYTES: {
-    const int64_t old = p.tile_bytes;
-    p.tile_bytes = value;
-    std::string err;
-    int rc;
-    try {
-      rc = hf::build_tiles(p, err);
-    } catch (const std::bad_alloc &) {
-      rc = HF_ENOMEM;
-      err = "out of host memory while tiling";
-    }
-    if (rc != HF_OK) {
-      p.tile_bytes = old;
-      std::string e2;
-      (void)hf::build_tiles(p, e2);
-      return fail(rc, err);
-    }
-    if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload(p);
-    return HF_OK;
-  }
+  case HF_PARAM_TILE_BYTES:
+    return retile(p, value);
   case HF_PARAM_GRID_WGS:
     if (value < 1 || value > 65536) return fail(HF_EINVAL, "grid workgroups must be in [1, 65536]");
     p.grid_wgs = value;
     return HF_OK;
   case HF_PARAM_VARIANT:
-    if (value < HF_VARIANT_PERSISTENT || value > HF_VARIANT_LDS_STAGED) return fail(HF_EINVAL, "unknown kernel variant");
+    if (value < HF_VARIANT_PERSISTENT || value > HF_VARIANT_PARTS) return fail(HF_EINVAL, "unknown kernel variant");
     p.variant = value;
+    return HF_OK;
+  case HF_PARAM_MULTICAST:
+    if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_CACHE_BLOCKED) return fail(HF_EINVAL, "unknown multicast mode");
+    p.multicast = value;
+    return HF_OK;
+  case HF_PARAM_MC_BLOCK_BYTES: {
+    if (value < (1 << 20) || value > (1ll << 30)) return fail(HF_EINVAL, "multicast block must be in [1 MiB, 1 GiB]");
+    p.mc_block_bytes = value;
+    return retile(p, p.tile_bytes);
+  }
+  case HF_PARAM_KIND_MASK:
+    if (value < 1 || value > 0x1F) return fail(HF_EINVAL, "kind mask must be in [1, 31]");
+    p.kind_mask = value;
+    return retile(p, p.tile_bytes);
+  case HF_PARAM_CACHE_POLICY:
+    if (value < -1 || value > 3) return fail(HF_EINVAL, "cache policy must be in [-1, 3]");
+    p.cache_policy = value;
+    return HF_OK;
+  case HF_PARAM_PART_BYTES:
+    if (value != 0 && value != 4096 && value != 8192 && value != 16384 && value != 32768)
+      return fail(HF_EINVAL, "part bytes must be 0 (automatic), 4096, 8192, 16384 or 32768");
+    p.part_bytes = value;
     return HF_OK;
   }
   return fail(HF_EINVAL, "unknown parameter");
@@ -168,6 +213,11 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_TILE_BYTES: return plan->p.tile_bytes;
   case HF_PARAM_GRID_WGS: return plan->p.grid_wgs;
   case HF_PARAM_VARIANT: return plan->p.variant;
+  case HF_PARAM_MULTICAST: return plan->p.multicast;
+  case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
+  case HF_PARAM_KIND_MASK: return plan->p.kind_mask;
+  case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;
+  case HF_PARAM_PART_BYTES: return plan->p.part_bytes;
   }
   return -1;
 }
@@ -256,14 +306,20 @@ int hf_plan_get_desc(const hf_plan *plan, int direction, size_t i, hf_desc *out)
 size_t hf_plan_bytes_moved(const hf_plan *plan, int direction) {
   if (!plan) return 0;
   size_t total = 0;
-  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) total += hf::desc_bytes(*desc_at(plan->p, direction, i));
+  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) {
+    const hf_desc *d = desc_at(plan->p, direction, i);
+    if ((plan->p.kind_mask >> d->kind) & 1) total += hf::desc_bytes(*d);
+  }
   return total;
 }
 
 size_t hf_plan_unique_src_bytes(const hf_plan *plan, int direction) {
   if (!plan) return 0;
   std::vector<const hf_desc *> v;
-  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) v.push_back(desc_at(plan->p, direction, i));
+  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) {
+    const hf_desc *d = desc_at(plan->p, direction, i);
+    if ((plan->p.kind_mask >> d->kind) & 1) v.push_back(d);
+  }
   return hf::unique_src_bytes(v);
 }
 
@@ -288,6 +344,8 @@ int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out) 
 size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
   if (!plan) return 0;
   const hf::Plan &p = plan->p;
+  if (direction == HF_DIR_TRAIN_TO_GEN && p.multicast == HF_MULTICAST_REGISTERS) return p.tiles_fwd_mc.size();
+  if (direction == HF_DIR_TRAIN_TO_GEN && p.multicast == HF_MULTICAST_CACHE_BLOCKED) return p.tiles_fwd_cb.size();
   if (direction == HF_DIR_TRAIN_TO_GEN) return (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   if (direction == HF_DIR_GEN_TO_TRAIN) return p.tiles_back.size();
   return 0;
@@ -296,7 +354,31 @@ size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
 int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out) {
   if (!plan || !out) return fail(HF_EINVAL, "null argument");
   if (i >= hf_plan_num_tiles(plan, direction)) return fail(HF_ERANGE, "no such tile");
-  *out = direction == HF_DIR_TRAIN_TO_GEN ? plan->p.tiles_fwd[i] : plan->p.tiles_back[i];
+  const hf::Plan &p = plan->p;
+  *out = direction == HF_DIR_GEN_TO_TRAIN                    ? p.tiles_back[i]
+         : p.multicast == HF_MULTICAST_REGISTERS             ? p.tiles_fwd_mc[i]
+         : p.multicast == HF_MULTICAST_CACHE_BLOCKED         ? p.tiles_fwd_cb[i]
+                                                              : p.tiles_fwd[i];
+  return HF_OK;
+}
+
+int hf_plan_get_tile_dst(const hf_plan *plan, int direction, size_t i, uint32_t k, uint64_t *out) {
+  hf_tile tl;
+  if (!out) return fail(HF_EINVAL, "null argument");
+  if (int rc = hf_plan_get_tile(plan, direction, i, &tl)) return rc;
+  if (k >= tl.n_dst) return fail(HF_ERANGE, "no such destination");
+  *out = k == 0 ? tl.dst_off : plan->p.mc_dst[tl.dst_list + k - 1];
+  return HF_OK;
+}
+
+int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
+  if (!src && !dst) return fail(HF_EINVAL, "null buffers");
+  if (bytes % 16 || (reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) % 16)
+    return fail(HF_EINVAL, "calibration copy needs 16-byte aligned pointers and size");
+  const char *s = static_cast<const char *>(src), *d = static_cast<const char *>(dst);
+  if (s && d && s < d + bytes && d < s + bytes) return fail(HF_EINVAL, "calibration copy: buffers overlap");
+  const int e = hf::launch_calib_copy(src, dst, bytes, hip_stream);
+  if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
 

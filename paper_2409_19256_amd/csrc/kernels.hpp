@@ -1,13 +1,19 @@
 // Launch interface between the C ABI and the device code.  Not part of the ABI.
 #pragma once
 #include <cstddef>
+#include <cstdint>
 
 #include "hfreshard.h"
 
 namespace hf {
 // Enqueues one kernel that executes tiles[0..n_tiles) (DEVICE pointer) on `stream`;
-// src/dst are the device buffers the tile offsets are relative to.  Returns a hipError_t
-// value (0 = success).  Never allocates or synchronises.
-int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const void *src, void *dst, int variant, int grid_wgs,
-                 void *stream);
+// extra_dst (DEVICE pointer, may be null if every tile has n_dst == 1) holds the
+// destinations 2..n_dst of multicast tiles; src/dst are the device buffers the tile
+// offsets are relative to.  tile_bytes = the tiler's tile size, part_bytes = payload per
+// workgroup of HF_VARIANT_PARTS (4096, 8192, 16384 or 32768).  Returns a hipError_t value
+// (0 = success).  Never allocates or synchronises.
+int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
+                 int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes, void *stream);
+// Plain grid-stride 16-byte copy (calibration); src == null: write only, dst == null: read only.
+int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 } // namespace hf

@@ -50,18 +50,32 @@ struct Plan {
   // step 4 (gen -> train): inverse of the own pieces
   std::vector<hf_desc> back;
 
-  // device work lists; tiles_fwd = [peer tiles | own tiles]
+  // device work lists; tiles_fwd = [peer tiles | own tiles], one destination per tile
   std::vector<hf_tile> tiles_fwd, tiles_back;
   size_t n_tiles_fwd_peer = 0;
+  // multicast work list for execute: descriptors that read the same training piece are
+  // tiled once; destinations 2..n of every tile are in mc_dst
+  std::vector<hf_tile> tiles_fwd_mc;
+  std::vector<uint64_t> mc_dst;
+  // the same work, one destination per tile, in cache-blocked order (see build_tiles)
+  std::vector<hf_tile> tiles_fwd_cb;
 
   int64_t tile_bytes = 128 * 1024;
   int64_t grid_wgs = 2048;
-  int64_t variant = HF_VARIANT_PERSISTENT;
+  int64_t variant = HF_VARIANT_PARTS;
+  int64_t multicast = HF_MULTICAST_CACHE_BLOCKED;
+  int64_t mc_block_bytes = 2 << 20;
+  int64_t cache_policy = -1; // auto
+  int64_t part_bytes = 0; // 0 = chosen per launch: 8 KiB for the cache-blocked list, else 4 KiB
+  int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (profiling aid)
 
   // device copy (null for HF_PLAN_HOST_ONLY)
   int device = -1;
   hf_tile *d_tiles_fwd = nullptr;
   hf_tile *d_tiles_back = nullptr;
+  hf_tile *d_tiles_fwd_mc = nullptr;
+  hf_tile *d_tiles_fwd_cb = nullptr;
+  uint64_t *d_mc_dst = nullptr;
 };
 
 // Builds everything except the device copy.  Returns HF_OK or an error, with `err` set.

@@ -16,6 +16,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <map>
 #include <numeric>
 #include <set>
 #include <tuple>
@@ -324,6 +325,7 @@ void push_tile(std::vector<hf_tile> &out, uint64_t src, uint64_t dst, uint32_t r
   uint64_t g = src | dst | row_bytes;
   if (rows > 1) g |= (uint64_t)sstr | dstr;
   tl.vec_bytes = vec_of(g);
+  tl.n_dst = 1;
   out.push_back(tl);
 }
 
@@ -370,10 +372,143 @@ int build_tiles(Plan &pl, std::string &err) {
   }
   pl.tiles_fwd.clear();
   pl.tiles_back.clear();
-  for (const hf_desc &d : pl.fwd_peer) tile_desc(pl.tiles_fwd, d, (uint64_t)pl.tile_bytes);
+  auto wanted = [&](const hf_desc &d) { return (pl.kind_mask >> d.kind) & 1; };
+  // one-destination lists in descriptor order, except that a run of row-parallel
+  // descriptors into the same destination tensor (its column stripes) is tiled round-robin,
+  // for the DRAM-row reason given at the multicast list below
+  auto tile_list = [&](const std::vector<hf_desc> &descs, std::vector<hf_tile> &out) {
+    std::vector<std::vector<hf_tile>> run;
+    for (size_t i = 0; i < descs.size();) {
+      if (!wanted(descs[i])) { ++i; continue; }
+      size_t j = i + 1;
+      if (descs[i].kind == HF_ROW)
+        while (j < descs.size() && descs[j].kind == HF_ROW && descs[j].dst_rank == descs[i].dst_rank &&
+               descs[j].tensor_id == descs[i].tensor_id && descs[j].layer == descs[i].layer)
+          ++j;
+      if (j == i + 1) {
+        tile_desc(out, descs[i], (uint64_t)pl.tile_bytes);
+      } else {
+        run.assign(j - i, {});
+        size_t longest = 0;
+        for (size_t k = i; k < j; ++k) {
+          tile_desc(run[k - i], descs[k], (uint64_t)pl.tile_bytes);
+          longest = std::max(longest, run[k - i].size());
+        }
+        for (size_t t = 0; t < longest; ++t)
+          for (auto &r : run)
+            if (t < r.size()) out.push_back(r[t]);
+      }
+      i = j;
+    }
+  };
+  tile_list(pl.fwd_peer, pl.tiles_fwd);
   pl.n_tiles_fwd_peer = pl.tiles_fwd.size();
-  for (const hf_desc &d : pl.fwd_own) tile_desc(pl.tiles_fwd, d, (uint64_t)pl.tile_bytes);
-  for (const hf_desc &d : pl.back) tile_desc(pl.tiles_back, d, (uint64_t)pl.tile_bytes);
+  tile_list(pl.fwd_own, pl.tiles_fwd);
+  tile_list(pl.back, pl.tiles_back);
+
+  // multicast list over the descriptors execute performs: same source bytes and same
+  // geometry -> one tile with several destinations, in order of first appearance
+  pl.tiles_fwd_mc.clear();
+  pl.mc_dst.clear();
+  {
+    std::vector<const hf_desc *> active;
+    for (const hf_desc &d : pl.fwd_peer) if (wanted(d)) active.push_back(&d);
+    if (pl.flags & HF_COPY_OWN)
+      for (const hf_desc &d : pl.fwd_own) if (wanted(d)) active.push_back(&d);
+    typedef std::tuple<uint64_t, uint32_t, uint32_t, uint32_t, uint64_t, uint64_t, uint64_t, uint64_t> Key;
+    std::map<Key, size_t> group_of;
+    std::vector<std::vector<const hf_desc *>> groups;
+    for (const hf_desc *d : active) {
+      const Key k{d->src_off, d->n_blocks, d->rows, d->row_bytes, d->src_block_stride, d->src_row_stride,
+                  d->dst_block_stride, d->dst_row_stride};
+      auto it = group_of.find(k);
+      if (it == group_of.end()) {
+        group_of[k] = groups.size();
+        groups.push_back({d});
+      } else {
+        groups[it->second].push_back(d);
+      }
+    }
+    // tiles of every group (destinations 2..n already appended to mc_dst)
+    std::vector<std::vector<hf_tile>> group_tiles(groups.size());
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+      const auto &grp_descs = groups[gi];
+      const hf_desc &d0 = *grp_descs[0];
+      tile_desc(group_tiles[gi], d0, (uint64_t)pl.tile_bytes);
+      for (hf_tile &tl : group_tiles[gi]) {
+        tl.n_dst = (uint32_t)grp_descs.size();
+        tl.dst_list = (uint32_t)pl.mc_dst.size();
+        uint64_t g = tl.vec_bytes; // already covers source, first destination, sizes, strides
+        for (size_t j = 1; j < grp_descs.size(); ++j) {
+          const uint64_t off = tl.dst_off - d0.dst_off + grp_descs[j]->dst_off;
+          pl.mc_dst.push_back(off);
+          g |= off;
+        }
+        tl.vec_bytes = vec_of(g);
+      }
+    }
+    // Row-parallel tensors: the a training pieces of one generation tensor are column
+    // stripes of the same destination rows.  Their tiles are emitted round-robin (rows
+    // 0..R of every piece, then the next rows of every piece, ...) so that each
+    // destination row is completed while it is still open in DRAM, instead of being
+    // visited once per stripe with a fraction of a row each time.
+    typedef std::tuple<int, int, int, int, int> SibKey; // tensor, layer, dp, gpp, gtp of the destination
+    std::map<SibKey, std::vector<size_t>> siblings;
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+      const hf_desc &d0 = *groups[gi][0];
+      if (d0.kind != HF_ROW) continue;
+      const Coords &c = pl.coords[d0.dst_rank];
+      siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}].push_back(gi);
+    }
+    std::vector<char> emitted(groups.size(), 0);
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+      if (emitted[gi]) continue;
+      const hf_desc &d0 = *groups[gi][0];
+      std::vector<size_t> set{gi};
+      if (d0.kind == HF_ROW) {
+        const Coords &c = pl.coords[d0.dst_rank];
+        set = siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}];
+      }
+      size_t longest = 0;
+      for (size_t g2 : set) { emitted[g2] = 1; longest = std::max(longest, group_tiles[g2].size()); }
+      for (size_t i = 0; i < longest; ++i)
+        for (size_t g2 : set)
+          if (i < group_tiles[g2].size()) pl.tiles_fwd_mc.push_back(group_tiles[g2][i]);
+    }
+    if (pl.mc_dst.size() >= (1ull << 32)) { err = "too many multicast destinations; raise the tile size"; return HF_ERANGE; }
+  }
+
+  // cache-blocked multicast order: the same work as one-destination tiles, arranged so that
+  // a block of at most mc_block_bytes of source is copied to its first destination, then
+  // the same block to the second, ...: only the first pass reads HBM, the later passes
+  // find the block in L2 (workgroups are handed out in list order, and the workgroup that
+  // copies a given source part runs on the same XCD in every pass because each pass spans
+  // a whole number of tiles with a fixed number of workgroups per tile).
+  pl.tiles_fwd_cb.clear();
+  {
+    std::vector<const hf_tile *> batch;
+    uint64_t batch_bytes = 0;
+    auto flush = [&]() {
+      if (batch.empty()) return;
+      for (uint32_t j = 0; j < batch[0]->n_dst; ++j)
+        for (const hf_tile *t : batch) {
+          hf_tile one = *t;
+          one.dst_off = j == 0 ? t->dst_off : pl.mc_dst[t->dst_list + j - 1];
+          one.n_dst = 1;
+          one.dst_list = 0;
+          pl.tiles_fwd_cb.push_back(one);
+        }
+      batch.clear();
+      batch_bytes = 0;
+    };
+    for (const hf_tile &t : pl.tiles_fwd_mc) {
+      const uint64_t payload = (uint64_t)t.rows * t.row_bytes;
+      if (!batch.empty() && (t.n_dst != batch[0]->n_dst || batch_bytes + payload > (uint64_t)pl.mc_block_bytes)) flush();
+      batch.push_back(&t);
+      batch_bytes += payload;
+    }
+    flush();
+  }
   if (pl.tiles_fwd.size() >= (1ull << 31) || pl.tiles_back.size() >= (1ull << 31)) {
     err = "too many tiles; raise the tile size";
     return HF_ERANGE;
@@ -439,6 +574,7 @@ int train_id_of(int gen_id) {
 } // namespace
 
 int validate_plan(const Plan &pl, std::string &err) {
+  if (pl.kind_mask != 0x1F) { err = "plan is restricted to some descriptor kinds (HF_PARAM_KIND_MASK)"; return HF_EINVAL; }
   // (1) every descriptor stays inside the payload of the tensors it names
   auto inside = [&](const hf_desc &d, bool forward) -> bool {
     const int train_rank = forward ? d.src_rank : d.dst_rank, gen_rank = forward ? d.dst_rank : d.src_rank;
@@ -486,6 +622,28 @@ int validate_plan(const Plan &pl, std::string &err) {
       !normalise(tf_peer, err, "peer tiles") || !normalise(fwd_peer_only, err, "peer descriptors"))
     return HF_ERANGE;
   if (!same(tf, fwd) || !same(tb, back) || !same(tf_peer, fwd_peer_only)) { err = "tiles differ from descriptors"; return HF_ERANGE; }
+  // the multicast list, expanded per destination, is the list execute would run one by one
+  std::vector<Seg> mc;
+  for (const hf_tile &t : pl.tiles_fwd_mc) {
+    if (t.n_dst == 0 || (t.n_dst > 1 && (uint64_t)t.dst_list + t.n_dst - 1 > pl.mc_dst.size())) { err = "multicast tile: bad destination list"; return HF_ERANGE; }
+    for (uint32_t k = 0; k < t.n_dst; ++k) {
+      hf_tile one = t;
+      one.dst_off = k == 0 ? t.dst_off : pl.mc_dst[t.dst_list + k - 1];
+      uint64_t g = one.src_off | one.dst_off | one.row_bytes;
+      if (one.rows > 1) g |= (uint64_t)one.src_row_stride | one.dst_row_stride;
+      if (g % t.vec_bytes) { err = "multicast tile alignment wrong"; return HF_ERANGE; }
+      tile_segments(one, mc);
+    }
+  }
+  if (!normalise(mc, err, "multicast tiles")) return HF_ERANGE;
+  if (!same(mc, (pl.flags & HF_COPY_OWN) ? fwd : fwd_peer_only)) { err = "multicast tiles differ from descriptors"; return HF_ERANGE; }
+  std::vector<Seg> cb;
+  for (const hf_tile &t : pl.tiles_fwd_cb) {
+    if (t.n_dst != 1) { err = "cache-blocked tile with several destinations"; return HF_ERANGE; }
+    tile_segments(t, cb);
+  }
+  if (!normalise(cb, err, "cache-blocked tiles")) return HF_ERANGE;
+  if (!same(cb, mc)) { err = "cache-blocked tiles differ from descriptors"; return HF_ERANGE; }
   for (const std::vector<hf_tile> *lst : {&pl.tiles_fwd, &pl.tiles_back})
     for (const hf_tile &t : *lst) {
       uint64_t g = t.src_off | t.dst_off | t.row_bytes;

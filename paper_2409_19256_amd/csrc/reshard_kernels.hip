@@ -7,8 +7,12 @@
 // are issued per lane before the first store so that each CU keeps tens of KiB in
 // flight, and the grid is a fixed number of persistent workgroups that stride over the
 // tile list (tile i -> workgroup i mod grid), which keeps the workgroups that run at the
-// same time on neighbouring tiles of the same tensors.  No MFMA: there is no arithmetic.
+// same time on neighbouring tiles of the same tensors.  A tile may name several
+// destinations (one training piece wanted by several ranks of a micro-DP group,
+// Section 5.3): it is loaded once and stored to each.  No MFMA: there is no arithmetic.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "hfreshard.h"
 #include "kernels.hpp"
@@ -18,86 +22,135 @@ namespace hf {
 namespace {
 
 constexpr int kWG = 256;    // threads per workgroup = 4 wavefronts of 64
-constexpr int kUnroll = 8;  // independent accesses in flight per lane
+constexpr int kWave = 64;
+constexpr int kMaxUnroll = 8;  // independent accesses in flight per lane (persistent kernels)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename V> __device__ __forceinline__ V load_stream(const char *p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
+// Cache policy of the streaming accesses: bit 0 = plain (temporal) loads, bit 1 = plain
+// stores; 0 = both non-temporal.  Every byte is touched once, so nothing is worth keeping
+// in L2; the policy is a launch parameter only so that the choice can be measured.
+template <typename V, int kPolicy> __device__ __forceinline__ V load_stream(const char *p) {
+  if constexpr (kPolicy & 1) return *reinterpret_cast<const V *>(p);
+  else return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
 }
-template <typename V> __device__ __forceinline__ void store_stream(char *p, V v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
+template <typename V, int kPolicy> __device__ __forceinline__ void store_stream(char *p, V v) {
+  if constexpr (kPolicy & 2) *reinterpret_cast<V *>(p) = v;
+  else __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
 }
 
-// rows x row_bytes, element (row, i) at base + row*stride + i on either side.
-// Vector index v in [0, rows*vpr) maps to row = v / vpr, column = v % vpr, so lanes of a
-// wavefront walk consecutive bytes of a row and spill into the next row at its end.
-template <typename V>
-__device__ __forceinline__ void copy_tile(const char *__restrict__ src, char *__restrict__ dst, uint32_t rows,
-                                          uint32_t row_bytes, uint32_t sstr, uint32_t dstr) {
-  const uint32_t vpr = row_bytes / (uint32_t)sizeof(V);
-  const uint32_t total = rows * vpr;
-  if (rows == 1) {
-    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += kUnroll * kWG) {
-      V v[kUnroll];
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const uint32_t i = i0 + k * kWG;
-        if (i < total) v[k] = load_stream<V>(src + (uint64_t)i * sizeof(V));
-      }
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const uint32_t i = i0 + k * kWG;
-        if (i < total) store_stream<V>(dst + (uint64_t)i * sizeof(V), v[k]);
-      }
-    }
-    return;
+// rows x row_bytes, byte (row, i) at base + row*stride + i on either side, copied by a
+// group of kGroup consecutive lanes (a workgroup or one wavefront); `lane` is the index
+// inside the group.  Vector index v in [0, rows*vpr) maps to row = v / vpr, column =
+// v % vpr, so the lanes of a wavefront walk consecutive bytes of a row and spill into
+// the next row at its end.  The loaded vectors are stored to n_dst destinations.
+// `part`/`part_bytes`: the group copies only bytes [part*part_bytes, (part+1)*part_bytes)
+// of the tile's payload (part_bytes == 0: the whole tile).
+template <typename V, int kGroup, int kPolicy, int kUnroll>
+__device__ __forceinline__ void copy_tile(const hf_tile &tl, const uint64_t *__restrict__ extra_dst,
+                                          const char *__restrict__ src_base, char *__restrict__ dst_base, uint32_t lane,
+                                          uint32_t part, uint32_t part_bytes) {
+  const char *__restrict__ src = src_base + tl.src_off;
+  const uint32_t rows = tl.rows, sstr = tl.src_row_stride, dstr = tl.dst_row_stride;
+  const uint32_t vpr = tl.row_bytes / (uint32_t)sizeof(V);
+  uint32_t total = rows * vpr, first = 0;
+  if (part_bytes) {
+    const uint32_t per = part_bytes / (uint32_t)sizeof(V);
+    first = min(part * per, total);
+    total = min(first + per, total);
   }
-  for (uint32_t i0 = threadIdx.x; i0 < total; i0 += kUnroll * kWG) {
+  for (uint32_t i0 = first + lane; i0 < total; i0 += kUnroll * kGroup) {
     V v[kUnroll];
     uint32_t doff[kUnroll];
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k) {
-      const uint32_t i = i0 + k * kWG;
-      const uint32_t row = i / vpr, col = (i - row * vpr) * (uint32_t)sizeof(V);
-      doff[k] = row * dstr + col; // tile extents stay far below 4 GiB
-      if (i < total) v[k] = load_stream<V>(src + (row * sstr + col));
+      const uint32_t i = i0 + k * kGroup;
+      uint32_t soff;
+      if (rows == 1) {
+        soff = doff[k] = i * (uint32_t)sizeof(V);
+      } else {
+        const uint32_t row = i / vpr, col = (i - row * vpr) * (uint32_t)sizeof(V);
+        soff = row * sstr + col; // the tiler keeps offsets inside a tile below 4 GiB
+        doff[k] = row * dstr + col;
+      }
+      if (i < total) v[k] = load_stream<V, kPolicy>(src + soff);
     }
+    for (uint32_t j = 0; j < tl.n_dst; ++j) { // uniform trip count
+      char *__restrict__ dst = dst_base + (j == 0 ? tl.dst_off : extra_dst[tl.dst_list + j - 1]);
 #pragma unroll
-    for (int k = 0; k < kUnroll; ++k)
-      if (i0 + k * kWG < total) store_stream<V>(dst + doff[k], v[k]);
+      for (int k = 0; k < kUnroll; ++k)
+        if (i0 + k * kGroup < total) store_stream<V, kPolicy>(dst + doff[k], v[k]);
+    }
   }
 }
 
-__device__ __forceinline__ void run_tile(const hf_tile &tl, const char *__restrict__ src, char *__restrict__ dst) {
-  const char *s = src + tl.src_off;
-  char *d = dst + tl.dst_off;
-  switch (tl.vec_bytes) { // uniform over the workgroup
-  case 16: copy_tile<u32x4>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride); break;
-  case 8: copy_tile<u32x2>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride); break;
-  case 4: copy_tile<uint32_t>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride); break;
-  default: copy_tile<uint16_t>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride); break;
+template <int kGroup, int kPolicy, int kUnroll = kMaxUnroll>
+__device__ __forceinline__ void run_tile(const hf_tile &tl, const uint64_t *__restrict__ extra_dst,
+                                         const char *__restrict__ src, char *__restrict__ dst, uint32_t lane,
+                                         uint32_t part = 0, uint32_t part_bytes = 0) {
+  switch (tl.vec_bytes) { // uniform over the group
+  case 16: copy_tile<u32x4, kGroup, kPolicy, kUnroll>(tl, extra_dst, src, dst, lane, part, part_bytes); break;
+  case 8: copy_tile<u32x2, kGroup, kPolicy, kUnroll>(tl, extra_dst, src, dst, lane, part, part_bytes); break;
+  case 4: copy_tile<uint32_t, kGroup, kPolicy, kUnroll>(tl, extra_dst, src, dst, lane, part, part_bytes); break;
+  default: copy_tile<uint16_t, kGroup, kPolicy, kUnroll>(tl, extra_dst, src, dst, lane, part, part_bytes); break;
   }
 }
 
 // Persistent workgroups: workgroup w copies tiles w, w+grid, w+2*grid, ...  Every
 // workgroup leaves the loop after at most ceil(n/grid) rounds; there is no waiting on
 // other workgroups anywhere.
+template <int kPolicy>
 __global__ __launch_bounds__(kWG) void reshard_persistent(const hf_tile *__restrict__ tiles, uint32_t n_tiles,
+                                                          const uint64_t *__restrict__ extra_dst,
                                                           const char *__restrict__ src, char *__restrict__ dst) {
   for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
     const hf_tile tl = tiles[t];
-    run_tile(tl, src, dst);
+    run_tile<kWG, kPolicy>(tl, extra_dst, src, dst, threadIdx.x);
   }
 }
 
+// Same, but every wavefront walks the list on its own: wavefront g of G copies tiles
+// g, g+G, ...  (wavefront-level dispatch; pair it with tiles of a few KiB to 32 KiB).
+template <int kPolicy>
+__global__ __launch_bounds__(kWG) void reshard_wave_persistent(const hf_tile *__restrict__ tiles, uint32_t n_tiles,
+                                                               const uint64_t *__restrict__ extra_dst,
+                                                               const char *__restrict__ src, char *__restrict__ dst) {
+  const uint32_t waves_per_wg = kWG / kWave;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave); // uniform -> scalar tile loads
+  const uint32_t g = blockIdx.x * waves_per_wg + wave, G = gridDim.x * waves_per_wg;
+  for (uint32_t t = g; t < n_tiles; t += G) {
+    const hf_tile tl = tiles[t];
+    run_tile<kWave, kPolicy>(tl, extra_dst, src, dst, threadIdx.x % kWave);
+  }
+}
+
+template <int kPolicy>
 __global__ __launch_bounds__(kWG) void reshard_one_tile(const hf_tile *__restrict__ tiles, uint32_t n_tiles,
+                                                        const uint64_t *__restrict__ extra_dst,
                                                         const char *__restrict__ src, char *__restrict__ dst) {
   const uint32_t t = blockIdx.x;
   if (t < n_tiles) {
     const hf_tile tl = tiles[t];
-    run_tile(tl, src, dst);
+    run_tile<kWG, kPolicy>(tl, extra_dst, src, dst, threadIdx.x);
+  }
+}
+
+// One short-lived workgroup per `part_bytes` of payload: workgroup b copies part b % parts
+// of tile b / parts and exits (parts = ceil(tile bytes / part_bytes), the same for every
+// tile; parts beyond the end of a short tile are empty).  The hardware dispatcher hands
+// out workgroups in index order, so at any moment the chip works on one narrow, moving
+// window of source and destination addresses, and a slow CU simply takes fewer
+// workgroups.  kUnroll = part_bytes / 4 KiB vectors per lane, all loaded before the
+// first store.
+template <int kPolicy, int kUnroll>
+__global__ __launch_bounds__(kWG) void reshard_parts(const hf_tile *__restrict__ tiles, uint32_t n_tiles, uint32_t parts,
+                                                     const uint64_t *__restrict__ extra_dst,
+                                                     const char *__restrict__ src, char *__restrict__ dst) {
+  const uint32_t t = blockIdx.x / parts, part = blockIdx.x - t * parts;
+  if (t < n_tiles) {
+    const hf_tile tl = tiles[t];
+    run_tile<kWG, kPolicy, kUnroll>(tl, extra_dst, src, dst, threadIdx.x, part, kUnroll * kWG * 16);
   }
 }
 
@@ -106,10 +159,12 @@ __global__ __launch_bounds__(kWG) void reshard_one_tile(const hf_tile *__restric
 // block-level permutations of this path (it moves the same HBM bytes).
 constexpr uint32_t kSlab = 16 * 1024;
 template <typename V>
-__device__ __forceinline__ void copy_tile_lds(const char *__restrict__ src, char *__restrict__ dst, uint32_t rows,
-                                              uint32_t row_bytes, uint32_t sstr, uint32_t dstr, char *lds) {
-  const uint32_t vpr = row_bytes / (uint32_t)sizeof(V);
-  const uint32_t total = rows * vpr;
+__device__ __forceinline__ void copy_tile_lds(const hf_tile &tl, const uint64_t *__restrict__ extra_dst,
+                                              const char *__restrict__ src_base, char *__restrict__ dst_base, char *lds) {
+  const char *__restrict__ src = src_base + tl.src_off;
+  const uint32_t sstr = tl.src_row_stride, dstr = tl.dst_row_stride;
+  const uint32_t vpr = tl.row_bytes / (uint32_t)sizeof(V);
+  const uint32_t total = tl.rows * vpr;
   constexpr uint32_t per_slab = kSlab / (uint32_t)sizeof(V);
   V *stage = reinterpret_cast<V *>(lds);
   for (uint32_t base = 0; base < total; base += per_slab) {
@@ -117,56 +172,118 @@ __device__ __forceinline__ void copy_tile_lds(const char *__restrict__ src, char
     for (uint32_t j = threadIdx.x; j < n; j += kWG) {
       const uint32_t i = base + j;
       const uint32_t row = i / vpr, col = (i - row * vpr) * (uint32_t)sizeof(V);
-      stage[j] = load_stream<V>(src + (row * sstr + col));
+      stage[j] = load_stream<V, 0>(src + (row * sstr + col));
     }
     __syncthreads();
-    for (uint32_t j = threadIdx.x; j < n; j += kWG) {
-      const uint32_t i = base + j;
-      const uint32_t row = i / vpr, col = (i - row * vpr) * (uint32_t)sizeof(V);
-      store_stream<V>(dst + (row * dstr + col), stage[j]);
+    for (uint32_t d = 0; d < tl.n_dst; ++d) {
+      char *__restrict__ dst = dst_base + (d == 0 ? tl.dst_off : extra_dst[tl.dst_list + d - 1]);
+      for (uint32_t j = threadIdx.x; j < n; j += kWG) {
+        const uint32_t i = base + j;
+        const uint32_t row = i / vpr, col = (i - row * vpr) * (uint32_t)sizeof(V);
+        store_stream<V, 0>(dst + (row * dstr + col), stage[j]);
+      }
     }
     __syncthreads();
   }
 }
 
 __global__ __launch_bounds__(kWG) void reshard_persistent_lds(const hf_tile *__restrict__ tiles, uint32_t n_tiles,
+                                                              const uint64_t *__restrict__ extra_dst,
                                                               const char *__restrict__ src, char *__restrict__ dst) {
   __shared__ __attribute__((aligned(16))) char lds[kSlab];
   for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
     const hf_tile tl = tiles[t];
-    const char *s = src + tl.src_off;
-    char *d = dst + tl.dst_off;
     switch (tl.vec_bytes) {
-    case 16: copy_tile_lds<u32x4>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride, lds); break;
-    case 8: copy_tile_lds<u32x2>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride, lds); break;
-    case 4: copy_tile_lds<uint32_t>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride, lds); break;
-    default: copy_tile_lds<uint16_t>(s, d, tl.rows, tl.row_bytes, tl.src_row_stride, tl.dst_row_stride, lds); break;
+    case 16: copy_tile_lds<u32x4>(tl, extra_dst, src, dst, lds); break;
+    case 8: copy_tile_lds<u32x2>(tl, extra_dst, src, dst, lds); break;
+    case 4: copy_tile_lds<uint32_t>(tl, extra_dst, src, dst, lds); break;
+    default: copy_tile_lds<uint16_t>(tl, extra_dst, src, dst, lds); break;
     }
+  }
+}
+
+__global__ __launch_bounds__(kWG) void calib_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n_vec) {
+  const size_t stride = (size_t)gridDim.x * kWG;
+  for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+// read-only and write-only counterparts of calib_copy (ceilings of one direction)
+__global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec, uint32_t *__restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * kWG;
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  // data dependent, practically never true: keeps the loads alive without a store stream
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;
+}
+__global__ __launch_bounds__(kWG) void calib_write(u32x4 *__restrict__ dst, size_t n_vec) {
+  const size_t stride = (size_t)gridDim.x * kWG;
+  const u32x4 v = {0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au};
+  for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) __builtin_nontemporal_store(v, dst + i);
+}
+
+template <int kPolicy>
+void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint64_t *extra_dst, const char *s, char *d,
+                   int variant, uint32_t tile_bytes, uint32_t part_bytes, hipStream_t st) {
+  switch (variant) {
+  case HF_VARIANT_PARTS: {
+    const uint32_t parts = (tile_bytes + part_bytes - 1) / part_bytes;
+    const dim3 g(n * parts);
+    switch (part_bytes / 4096) {
+    case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    }
+    break;
+  }
+  case HF_VARIANT_ONE_WG_PER_TILE:
+    hipLaunchKernelGGL(reshard_one_tile<kPolicy>, dim3(n), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
+    break;
+  case HF_VARIANT_WAVE_PERSISTENT:
+    hipLaunchKernelGGL(reshard_wave_persistent<kPolicy>, dim3(grid), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
+    break;
+  default:
+    hipLaunchKernelGGL(reshard_persistent<kPolicy>, dim3(grid), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
+    break;
   }
 }
 
 } // namespace
 
-int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const void *src, void *dst, int variant, int grid_wgs,
-                 void *stream) {
+int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
+                 int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes, void *stream) {
   if (n_tiles == 0) return 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char *s = static_cast<const char *>(src);
   char *d = static_cast<char *>(dst);
   const uint32_t n = (uint32_t)n_tiles;
-  switch (variant) {
-  case HF_VARIANT_ONE_WG_PER_TILE:
-    hipLaunchKernelGGL(reshard_one_tile, dim3(n), dim3(kWG), 0, st, d_tiles, n, s, d);
-    break;
-  case HF_VARIANT_LDS_STAGED:
-    hipLaunchKernelGGL(reshard_persistent_lds, dim3((uint32_t)std::min<size_t>(n_tiles, (size_t)grid_wgs)), dim3(kWG), 0, st,
-                       d_tiles, n, s, d);
-    break;
-  default:
-    hipLaunchKernelGGL(reshard_persistent, dim3((uint32_t)std::min<size_t>(n_tiles, (size_t)grid_wgs)), dim3(kWG), 0, st,
-                       d_tiles, n, s, d);
-    break;
+  const uint32_t grid = (uint32_t)std::min<size_t>(n_tiles, (size_t)grid_wgs);
+  if (variant == HF_VARIANT_PARTS &&
+      (uint64_t)n * ((tile_bytes + part_bytes - 1) / part_bytes) > 0x7FFFFFFFull)
+    return (int)hipErrorInvalidValue; // grid too large: use bigger parts or smaller tiles
+  if (variant == HF_VARIANT_LDS_STAGED) {
+    hipLaunchKernelGGL(reshard_persistent_lds, dim3(grid), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
+  } else {
+    switch (cache_policy) {
+    case 1: launch_policy<1>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+    case 2: launch_policy<2>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+    case 3: launch_policy<3>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+    default: launch_policy<0>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+    }
   }
+  return (int)hipGetLastError();
+}
+
+int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {
+  if (bytes == 0) return 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (src && dst)
+    hipLaunchKernelGGL(calib_copy, dim3(4096), dim3(kWG), 0, st, static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), bytes / 16);
+  else if (src) // read only; the first 4 bytes of src double as the (never written) sink
+    hipLaunchKernelGGL(calib_read, dim3(4096), dim3(kWG), 0, st, static_cast<const u32x4 *>(src), bytes / 16,
+                       reinterpret_cast<uint32_t *>(const_cast<void *>(src)));
+  else
+    hipLaunchKernelGGL(calib_write, dim3(4096), dim3(kWG), 0, st, static_cast<u32x4 *>(dst), bytes / 16);
   return (int)hipGetLastError();
 }
 

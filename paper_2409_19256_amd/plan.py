@@ -31,7 +31,11 @@ class Plan:
             B.hf_plan_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the binding module may already be gone
+            pass
 
     def __enter__(self):
         return self
@@ -120,12 +124,18 @@ class Plan:
     def num_tiles(self, direction: int) -> int:
         return B.hf_plan_num_tiles(self._h, direction)
 
-    def tiles(self, direction: int) -> List[B.hf_tile]:
+    def tiles(self, direction: int):
+        """[(hf_tile, [destination offsets])] of the active work list of a direction."""
         res = []
+        off = C.c_uint64()
         for i in range(self.num_tiles(direction)):
             t = B.hf_tile()
             B.check(B.hf_plan_get_tile(self._h, direction, i, C.byref(t)), "hf_plan_get_tile")
-            res.append(t)
+            dsts = []
+            for k in range(t.n_dst):
+                B.check(B.hf_plan_get_tile_dst(self._h, direction, i, k, C.byref(off)), "hf_plan_get_tile_dst")
+                dsts.append(off.value)
+            res.append((t, dsts))
         return res
 
     def bytes_moved(self, direction: int) -> int:

@@ -14,8 +14,11 @@ def run_descs(descs, src_u8: np.ndarray, dst_u8: np.ndarray) -> None:
 
 
 def run_tiles(tiles, src_u8: np.ndarray, dst_u8: np.ndarray) -> None:
-    for tl in tiles:
+    """tiles: [(hf_tile, [destination offsets])] as Plan.tiles() returns them."""
+    for tl, dsts in tiles:
+        assert len(dsts) == tl.n_dst >= 1 and dsts[0] == tl.dst_off
         for r in range(tl.rows):
             s = tl.src_off + r * tl.src_row_stride
-            t = tl.dst_off + r * tl.dst_row_stride
-            dst_u8[t:t + tl.row_bytes] = src_u8[s:s + tl.row_bytes]
+            for d in dsts:
+                t = d + r * tl.dst_row_stride
+                dst_u8[t:t + tl.row_bytes] = src_u8[s:s + tl.row_bytes]

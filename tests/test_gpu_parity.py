@@ -63,8 +63,13 @@ def _d2h(t):
     return t.cpu().numpy().view(np.uint16)
 
 
-VARIANTS = [(B.HF_VARIANT_PERSISTENT, 128 * 1024, 2048), (B.HF_VARIANT_PERSISTENT, 4096, 7),
-            (B.HF_VARIANT_ONE_WG_PER_TILE, 64 * 1024, 1), (B.HF_VARIANT_LDS_STAGED, 128 * 1024, 512)]
+# (kernel variant, tile bytes, persistent grid or bytes per workgroup, multicast)
+VARIANTS = [(B.HF_VARIANT_PERSISTENT, 128 * 1024, 2048, 1), (B.HF_VARIANT_PERSISTENT, 4096, 7, 0),
+            (B.HF_VARIANT_ONE_WG_PER_TILE, 64 * 1024, 1, 1), (B.HF_VARIANT_LDS_STAGED, 128 * 1024, 512, 1),
+            (B.HF_VARIANT_WAVE_PERSISTENT, 16 * 1024, 1024, 1), (B.HF_VARIANT_WAVE_PERSISTENT, 8192, 3, 0),
+            (B.HF_VARIANT_PARTS, 32 * 1024, 4096, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 16384, 0),
+            (B.HF_VARIANT_PARTS, 12288, 8192, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 4096, 2),
+            (B.HF_VARIANT_PERSISTENT, 64 * 1024, 1024, 2)]
 
 
 @pytest.mark.parametrize("case", SMALL + [BASELINE[0]] + MEDIUM, ids=lambda c: c["name"])
@@ -77,13 +82,19 @@ def test_whole_buffers_match_oracle(case):
     pay, own = _payload_mask(orc, ranks, "gen"), _own_mask(orc, ranks)
     remote = pay & ~own
     tpay = _payload_mask(orc, ranks, "train")
-    for variant, tile_bytes, grid in VARIANTS:
-        _say(f"[case {case['name']} variant {variant} tile {tile_bytes} grid {grid}]")
+    for variant, tile_bytes, grid, multicast in VARIANTS:
+        _say(f"[case {case['name']} variant {variant} tile {tile_bytes} grid {grid} multicast {multicast}]")
         # --- COPY_OWN: complete generation buffers, padding untouched
         with make_plan(case, B.HF_COPY_OWN) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
-            pl.set_param(B.HF_PARAM_GRID_WGS, grid)
+            if variant == B.HF_VARIANT_PARTS:
+                pl.set_param(B.HF_PARAM_PART_BYTES, grid)      # third field = bytes per workgroup
+            else:
+                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
             pl.set_param(B.HF_PARAM_VARIANT, variant)
+            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+            if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
+                pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
             ar.gen.fill_(_i16(POISON))
@@ -94,8 +105,14 @@ def test_whole_buffers_match_oracle(case):
         # --- SKIP_OWN: only remote pieces written; install_own + execute = complete; reverse
         with make_plan(case, 0) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
-            pl.set_param(B.HF_PARAM_GRID_WGS, grid)
+            if variant == B.HF_VARIANT_PARTS:
+                pl.set_param(B.HF_PARAM_PART_BYTES, grid)      # third field = bytes per workgroup
+            else:
+                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
             pl.set_param(B.HF_PARAM_VARIANT, variant)
+            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+            if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
+                pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
             assert pl.bytes_moved(0) == 2 * int(remote.sum())
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
@@ -163,6 +180,36 @@ def test_vanilla_grouping_on_gpu():
         assert np.array_equal(_d2h(ar.gen), want)
         with pytest.raises(B.HfError):
             ar.back()
+
+
+def test_cache_policies_and_calibration_copies():
+    case = MEDIUM[1]
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 8)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    with make_plan(case, B.HF_COPY_OWN) as pl:
+        ar = Arena(pl)
+        ar.train.copy_(torch.from_numpy(train.view(np.int16)))
+        for policy in (1, 2, 3):
+            pl.set_param(B.HF_PARAM_CACHE_POLICY, policy)
+            ar.gen.fill_(_i16(POISON))
+            ar.execute()
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want), policy
+        # calibration kernels: copy is exact, read-only leaves the data alone, write-only fills
+        n = ar.train.numel() // 8 * 8
+        dst = ar.gen[:n]
+        st = Arena.stream_handle()
+        B.check(B.hf_calib_copy(ar.train.data_ptr(), dst.data_ptr(), 2 * n, st), "copy")
+        torch.cuda.synchronize()
+        assert torch.equal(dst, ar.train[:n])
+        B.check(B.hf_calib_copy(ar.train.data_ptr(), None, 2 * n, st), "read")
+        torch.cuda.synchronize()
+        assert np.array_equal(_d2h(ar.train), train)
+        B.check(B.hf_calib_copy(None, dst.data_ptr(), 2 * n, st), "write")
+        torch.cuda.synchronize()
+        assert bool((dst == 0x5A5A).all())
 
 
 def test_runtime_argument_errors():

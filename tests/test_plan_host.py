@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert C.sizeof(B.hf_desc) == 88 and C.sizeof(B.hf_tile) == 40 and C.sizeof(B.hf_tensor_info) == 32
+    assert C.sizeof(B.hf_desc) == 88 and C.sizeof(B.hf_tile) == 48 and C.sizeof(B.hf_tensor_info) == 32
     assert C.sizeof(B.hf_model_desc) == 36 and C.sizeof(B.hf_gen_layout) == 32
 
 
@@ -77,8 +77,8 @@ def _own_mask(orc, ranks):
 
 @pytest.mark.parametrize("case", CASES, ids=IDS)
 @pytest.mark.parametrize("use_tiles", [False, True], ids=["descs", "tiles"])
-@pytest.mark.parametrize("tile_bytes", [128 * 1024, 4096])
-def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes):
+@pytest.mark.parametrize("tile_bytes,multicast", [(128 * 1024, 2), (128 * 1024, 1), (4096, 1), (4096, 0), (8192, 2)])
+def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes, multicast):
     orc = make_oracle(case)
     ranks = list(range(orc.n_ranks))
     train = seeded_train_buf(orc, 4321)
@@ -89,6 +89,7 @@ def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes):
     # COPY_OWN: the whole generation buffer, padding untouched
     with make_plan(case, HOST | B.HF_COPY_OWN) as pl:
         pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+        pl.set_param(B.HF_PARAM_MULTICAST, multicast)
         pl.validate()
         items = pl.tiles(0) if use_tiles else pl.descs(0)
         got = np.full(want.shape, POISON, np.uint16)
@@ -99,6 +100,7 @@ def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes):
     # SKIP_OWN: only remote pieces are written; canaries on own pieces and padding survive
     with make_plan(case, HOST) as pl:
         pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+        pl.set_param(B.HF_PARAM_MULTICAST, multicast)
         pl.validate()
         items = pl.tiles(0) if use_tiles else pl.descs(0)
         got = np.full(want.shape, CANARY, np.uint16)
@@ -162,6 +164,64 @@ def test_own_view_is_where_the_oracle_finds_the_own_shard(case):
             assert (got_lo[other] == 0xFFFF).all() and (got_hi[other] == 0xFFFF).all()
             # every element of the training shard is in the view (zero redundancy)
             assert int(own.sum()) == sum(e.n for e in orc.train_table(r)[0])
+
+
+def test_multicast_tiles_read_every_training_piece_once():
+    """Llama-7B TP8->TP2: every training piece is wanted by the d_g-1 = 3 other ranks of
+    its micro-DP group, so the multicast list has a third of the tiles, all with 3
+    destinations; with HF_COPY_OWN all 4 ranks of the group take it."""
+    case = BASELINE[1]
+    for flags, n_dst in [(HOST, 3), (HOST | B.HF_COPY_OWN, 4)]:
+        with make_plan(case, flags) as pl:
+            pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)
+            t = B.hf_tile()
+            n = pl.num_tiles(0)
+            src_bytes = dst_bytes = singles = 0
+            for i in range(0, n):
+                B.check(B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)), "get_tile")
+                norm = t.rows == 1 and t.row_bytes == 2 * case["model"].hidden
+                # norm vectors are replicated: with HF_COPY_OWN every rank copies its own, once
+                assert t.n_dst == (1 if norm and flags & B.HF_COPY_OWN else n_dst)
+                singles += t.n_dst == 1
+                src_bytes += t.rows * t.row_bytes
+                dst_bytes += t.n_dst * t.rows * t.row_bytes
+            assert src_bytes == pl.unique_src_bytes(0) and dst_bytes == pl.bytes_moved(0)
+            pl.set_param(B.HF_PARAM_MULTICAST, 0)
+            assert pl.num_tiles(0) == (n - singles) * n_dst + singles
+
+
+def test_cache_blocked_order_repeats_each_source_block_per_destination():
+    """Default train->gen work list of Llama-7B TP8->TP2: blocks of at most 16 MiB of source,
+    each block listed d_g-1 = 3 times in a row with the same sources and different
+    destinations, so that passes 2 and 3 can be served by L2."""
+    with make_plan(BASELINE[1], HOST) as pl:
+        assert pl.get_param(B.HF_PARAM_MULTICAST) == B.HF_MULTICAST_CACHE_BLOCKED
+        block = pl.get_param(B.HF_PARAM_MC_BLOCK_BYTES)
+        n = pl.num_tiles(0)
+        t = B.hf_tile()
+
+        def tile(i):
+            B.check(B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)), "get_tile")
+            assert t.n_dst == 1
+            return (t.src_off, t.rows, t.row_bytes, t.src_row_stride), t.dst_off, t.rows * t.row_bytes
+
+        i = blocks = 0
+        while i < min(n, 40000):
+            first = tile(i)[0]
+            k = 1
+            while tile(i + k)[0] != first:
+                k += 1
+            srcs = [tile(i + x)[0] for x in range(k)]
+            assert len(set(srcs)) == k and sum(tile(i + x)[2] for x in range(k)) <= block
+            dsts = [tile(i + x)[1] for x in range(k)]
+            for p_ in (1, 2):
+                assert [tile(i + p_ * k + x)[0] for x in range(k)] == srcs
+                assert set(tile(i + p_ * k + x)[1] for x in range(k)).isdisjoint(dsts)
+            i += 3 * k
+            blocks += 1
+        assert blocks > 5
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_OFF)
+        assert pl.num_tiles(0) == n
 
 
 def test_vanilla_grouping_plan():
@@ -268,6 +328,17 @@ def test_error_codes():
             pl.set_param(B.HF_PARAM_GRID_WGS, 0)
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_VARIANT, 9)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_MULTICAST, 3)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_CACHE_POLICY, 4)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_PART_BYTES, 12288)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 4096)
+        assert B.hf_calib_copy(None, None, 16, None) == B.HF_EINVAL
+        assert B.hf_calib_copy(256, 4096, 24, None) == B.HF_EINVAL
+        assert B.hf_calib_copy(256, 512, 1024, None) == B.HF_EINVAL      # overlap
         d = B.hf_desc()
         assert B.hf_plan_get_desc(pl._h, 0, 10 ** 9, C.byref(d)) == B.HF_ERANGE
         t = B.hf_tensor_info()
