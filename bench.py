@@ -33,7 +33,22 @@ CONFIGS = {
 }
 
 
-def cpu_baseline(cfg, seconds_target=15.0):
+def measured_traffic(workload, default_config):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload (a
+    separate profiling run of the same launch configuration); None if there is none or if
+    this run does not use the default configuration the counters were taken with."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not default_config or not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=")
+            vals[k.strip()] = int(v)
+    return vals.get("fetch_bytes_per_launch", 0) + vals.get("write_bytes_per_launch", 0) or None
+
+
+def cpu_baseline(cfg, alg_per_written_byte, seconds_target=15.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: whole
     layers of all materialised generation ranks until about `seconds_target` s are spent."""
     import numpy as np
@@ -77,9 +92,11 @@ def cpu_baseline(cfg, seconds_target=15.0):
         layers_done += 1
         if spent >= seconds_target:
             break
-    return {"value": round(2 * moved / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"oracle concat+slice of layers 0..{layers_done - 1} for all {len(ranks)} generation ranks of "
-                      f"{cfg['name']} ({2 * moved / 1e9:.2f} GB read+write by the GPU path's accounting) in {spent:.1f} s, numpy, 1 thread"}
+    alg = alg_per_written_byte * moved       # same byte accounting as the GPU figure
+    return {"value": round(alg / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"oracle (rebuild full tensors from all shards, slice) on layers 0..{layers_done - 1} of {orc.m.n_layers} for all "
+                      f"{len(ranks)} generation ranks of {cfg['name']}: {moved / 1e9:.2f} GB of remote pieces produced, "
+                      f"{alg / 1e9:.2f} GB by the GPU figure's read+write accounting, in {spent:.1f} s; numpy, 1 thread"}
 
 
 def main():
@@ -116,6 +133,8 @@ def main():
         print("bench.py: no GPU visible; the reshard library has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = dict(CONFIGS[args.config], index=args.config)
+    default_config = (args.direction == "fwd" and args.flags == "skip_own" and args.variant is None and args.tile_bytes is None
+                      and args.grid is None and args.multicast is None and not args.part_bytes and not args.mc_block_bytes)
     flags = B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN
     t0 = time.perf_counter()
     plan = Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags, mat_ranks=cfg["mat"])
@@ -188,7 +207,8 @@ def main():
         "pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "plan_build_upload_ms": round(plan_ms, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic(cfg["name"], default_config),
                      "kernel": ["reshard_persistent", "reshard_one_tile", "reshard_persistent_lds", "reshard_wave_persistent",
                                 "reshard_parts"][plan.get_param(B.HF_PARAM_VARIANT)],
                      "algorithmic_bytes_per_launch": alg_bytes,
@@ -197,7 +217,7 @@ def main():
     if not args.no_cpu_baseline:
         del ar
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(cfg)
+        out["cpu_baseline"] = cpu_baseline(cfg, alg_bytes / W)
     print(json.dumps(out), flush=True)
 
 
