@@ -173,8 +173,9 @@ HF_API void hf_plan_destroy(hf_plan *plan);
  * train_buf / gen_buf: DEVICE pointers, 256-byte aligned, at least
  * hf_plan_train_bytes / hf_plan_gen_bytes long, not overlapping; they may be two
  * offsets into one allocation.  hip_stream: a hipStream_t (NULL = default stream).
- * The calls enqueue one kernel launch on that stream and return; they never allocate,
- * synchronise or touch host copies of the buffers.  Padding between tensors is never
+ * The calls enqueue one kernel launch on that stream (a few for work lists beyond
+ * 16.7 million workgroups, see HF_PARAM_MAX_WGS_PER_LAUNCH) and return; they never
+ * allocate, synchronise or touch host copies of the buffers.  Padding between tensors is never
  * written.
  *
  * hf_reshard_execute (Section 5.2 step 1; Section 5.4): fills the generation buffers
@@ -206,7 +207,10 @@ enum {
   HF_PARAM_VARIANT = 2,      /* HF_VARIANT_*                                              */
   HF_PARAM_MULTICAST = 3,    /* HF_MULTICAST_*: how train->gen serves a training piece that
                                 several ranks of a micro-DP group want.  Same result in
-                                every mode; the modes differ in HBM reads.               */
+                                every mode; the modes differ in HBM reads.  When no piece
+                                of the plan has more than one destination (e.g. only one
+                                rank per micro-DP group is materialised) every mode runs
+                                as HF_MULTICAST_OFF, and hf_plan_get_param says so.      */
   HF_PARAM_CACHE_POLICY = 4, /* -1 (default): chosen by the library (non-temporal loads and
                                 stores; plain loads under HF_MULTICAST_CACHE_BLOCKED);
                                 0: both non-temporal; bit 0: plain loads; bit 1: plain
@@ -216,6 +220,10 @@ enum {
                                 train->gen list and 4096 otherwise                       */
   HF_PARAM_MC_BLOCK_BYTES = 6, /* HF_MULTICAST_CACHE_BLOCKED: source bytes per block,
                                 1 MiB .. 1 GiB, default 2 MiB (re-tiles and re-uploads)  */
+  HF_PARAM_MAX_WGS_PER_LAUNCH = 8, /* HF_VARIANT_PARTS / ONE_WG_PER_TILE: a work list that needs
+                                more workgroups goes out in several launches of at most this
+                                many, in list order; 1024 .. 16777215 (default: a HIP grid
+                                holds fewer than 2^32 threads)                            */
   HF_PARAM_KIND_MASK = 7     /* profiling aid: bit k set = descriptors of kind k (HF_COL ..
                                 HF_GATEUP_DEINT) are executed and counted by
                                 hf_plan_bytes_moved / hf_plan_unique_src_bytes; default 31

@@ -101,7 +101,7 @@ int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *ex
   // L2, 4 KiB for plain one-to-one copies
   const uint32_t part = p.part_bytes ? (uint32_t)p.part_bytes : (temporal_loads ? 8192u : 4096u);
   const int e = hf::launch_tiles(tiles, n, extra_dst, src, dst, (int)p.variant, (int)p.grid_wgs, policy,
-                                 (uint32_t)p.tile_bytes, part, stream);
+                                 (uint32_t)p.tile_bytes, part, (uint32_t)p.max_wgs_per_launch, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
@@ -144,9 +144,9 @@ void hf_plan_destroy(hf_plan *plan) {
 int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
-  if (p.multicast == HF_MULTICAST_REGISTERS)
+  if (p.effective_multicast() == HF_MULTICAST_REGISTERS)
     return launch(p, p.d_tiles_fwd_mc, p.tiles_fwd_mc.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream);
-  if (p.multicast == HF_MULTICAST_CACHE_BLOCKED)
+  if (p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED)
     return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, true);
   const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream);
@@ -190,6 +190,10 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     p.mc_block_bytes = value;
     return retile(p, p.tile_bytes);
   }
+  case HF_PARAM_MAX_WGS_PER_LAUNCH:
+    if (value < 1024 || value > 0xFFFFFFFFll / 256) return fail(HF_EINVAL, "workgroups per launch must be in [1024, 16777215]");
+    p.max_wgs_per_launch = value;
+    return HF_OK;
   case HF_PARAM_KIND_MASK:
     if (value < 1 || value > 0x1F) return fail(HF_EINVAL, "kind mask must be in [1, 31]");
     p.kind_mask = value;
@@ -213,9 +217,10 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_TILE_BYTES: return plan->p.tile_bytes;
   case HF_PARAM_GRID_WGS: return plan->p.grid_wgs;
   case HF_PARAM_VARIANT: return plan->p.variant;
-  case HF_PARAM_MULTICAST: return plan->p.multicast;
+  case HF_PARAM_MULTICAST: return plan->p.effective_multicast();
   case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
   case HF_PARAM_KIND_MASK: return plan->p.kind_mask;
+  case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;
   case HF_PARAM_PART_BYTES: return plan->p.part_bytes;
   }
@@ -344,8 +349,8 @@ int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out) 
 size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
   if (!plan) return 0;
   const hf::Plan &p = plan->p;
-  if (direction == HF_DIR_TRAIN_TO_GEN && p.multicast == HF_MULTICAST_REGISTERS) return p.tiles_fwd_mc.size();
-  if (direction == HF_DIR_TRAIN_TO_GEN && p.multicast == HF_MULTICAST_CACHE_BLOCKED) return p.tiles_fwd_cb.size();
+  if (direction == HF_DIR_TRAIN_TO_GEN && p.effective_multicast() == HF_MULTICAST_REGISTERS) return p.tiles_fwd_mc.size();
+  if (direction == HF_DIR_TRAIN_TO_GEN && p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED) return p.tiles_fwd_cb.size();
   if (direction == HF_DIR_TRAIN_TO_GEN) return (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   if (direction == HF_DIR_GEN_TO_TRAIN) return p.tiles_back.size();
   return 0;
@@ -356,8 +361,8 @@ int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out)
   if (i >= hf_plan_num_tiles(plan, direction)) return fail(HF_ERANGE, "no such tile");
   const hf::Plan &p = plan->p;
   *out = direction == HF_DIR_GEN_TO_TRAIN                    ? p.tiles_back[i]
-         : p.multicast == HF_MULTICAST_REGISTERS             ? p.tiles_fwd_mc[i]
-         : p.multicast == HF_MULTICAST_CACHE_BLOCKED         ? p.tiles_fwd_cb[i]
+         : p.effective_multicast() == HF_MULTICAST_REGISTERS     ? p.tiles_fwd_mc[i]
+         : p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb[i]
                                                               : p.tiles_fwd[i];
   return HF_OK;
 }

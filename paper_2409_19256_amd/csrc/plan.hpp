@@ -59,6 +59,10 @@ struct Plan {
   std::vector<uint64_t> mc_dst;
   // the same work, one destination per tile, in cache-blocked order (see build_tiles)
   std::vector<hf_tile> tiles_fwd_cb;
+  bool has_sharing = false; // some training piece has more than one destination
+  // multicast mode that execute really uses: without sharing the multicast lists are the
+  // one-destination work in another order, and the plain list with streaming loads is faster
+  int64_t effective_multicast() const { return has_sharing ? multicast : (int64_t)HF_MULTICAST_OFF; }
 
   int64_t tile_bytes = 128 * 1024;
   int64_t grid_wgs = 2048;
@@ -67,6 +71,7 @@ struct Plan {
   int64_t mc_block_bytes = 2 << 20;
   int64_t cache_policy = -1; // auto
   int64_t part_bytes = 0; // 0 = chosen per launch: 8 KiB for the cache-blocked list, else 4 KiB
+  int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
   int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (profiling aid)
 
   // device copy (null for HF_PLAN_HOST_ONLY)

@@ -429,6 +429,8 @@ int build_tiles(Plan &pl, std::string &err) {
         groups[it->second].push_back(d);
       }
     }
+    pl.has_sharing = false;
+    for (const auto &g : groups) pl.has_sharing = pl.has_sharing || g.size() > 1;
     // tiles of every group (destinations 2..n already appended to mc_dst)
     std::vector<std::vector<hf_tile>> group_tiles(groups.size());
     for (size_t gi = 0; gi < groups.size(); ++gi) {

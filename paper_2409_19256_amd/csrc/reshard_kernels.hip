@@ -251,27 +251,41 @@ void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint
 } // namespace
 
 int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
-                 int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes, void *stream) {
+                 int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes,
+                 uint32_t max_wgs_per_launch, void *stream) {
   if (n_tiles == 0) return 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char *s = static_cast<const char *>(src);
   char *d = static_cast<char *>(dst);
-  const uint32_t n = (uint32_t)n_tiles;
-  const uint32_t grid = (uint32_t)std::min<size_t>(n_tiles, (size_t)grid_wgs);
-  if (variant == HF_VARIANT_PARTS &&
-      (uint64_t)n * ((tile_bytes + part_bytes - 1) / part_bytes) > 0x7FFFFFFFull)
-    return (int)hipErrorInvalidValue; // grid too large: use bigger parts or smaller tiles
-  if (variant == HF_VARIANT_LDS_STAGED) {
-    hipLaunchKernelGGL(reshard_persistent_lds, dim3(grid), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
-  } else {
-    switch (cache_policy) {
-    case 1: launch_policy<1>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-    case 2: launch_policy<2>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-    case 3: launch_policy<3>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-    default: launch_policy<0>(d_tiles, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-    }
+  // A HIP grid holds fewer than 2^32 threads per dimension (a larger one is not refused,
+  // its size wraps), so the kernels that take one workgroup per tile or per part go out
+  // in several launches of at most max_wgs_per_launch workgroups, in list order.
+  size_t tiles_per_launch = n_tiles;
+  if (variant == HF_VARIANT_PARTS) {
+    const uint32_t parts = (tile_bytes + part_bytes - 1) / part_bytes;
+    if (parts > max_wgs_per_launch) return (int)hipErrorInvalidValue;
+    tiles_per_launch = max_wgs_per_launch / parts;
+  } else if (variant == HF_VARIANT_ONE_WG_PER_TILE) {
+    tiles_per_launch = max_wgs_per_launch;
   }
-  return (int)hipGetLastError();
+  for (size_t first = 0; first < n_tiles; first += tiles_per_launch) {
+    const uint32_t n = (uint32_t)std::min(tiles_per_launch, n_tiles - first);
+    const uint32_t grid = (uint32_t)std::min<size_t>(n, (size_t)grid_wgs);
+    const hf_tile *t = d_tiles + first;
+    if (variant == HF_VARIANT_LDS_STAGED) {
+      hipLaunchKernelGGL(reshard_persistent_lds, dim3(grid), dim3(kWG), 0, st, t, n, extra_dst, s, d);
+    } else {
+      switch (cache_policy) {
+      case 1: launch_policy<1>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+      case 2: launch_policy<2>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+      case 3: launch_policy<3>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+      default: launch_policy<0>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+      }
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
 }
 
 int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {

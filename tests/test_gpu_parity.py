@@ -212,6 +212,30 @@ def test_cache_policies_and_calibration_copies():
         assert bool((dst == 0x5A5A).all())
 
 
+def test_work_lists_longer_than_one_grid_are_split_into_launches():
+    """A HIP grid holds fewer than 2^32 threads; longer work lists must go out in several
+    launches.  Forced here with a tiny per-launch limit on a medium shape."""
+    case = MEDIUM[0]
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 12)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    for variant, mc in [(B.HF_VARIANT_PARTS, 2), (B.HF_VARIANT_PARTS, 0), (B.HF_VARIANT_ONE_WG_PER_TILE, 1)]:
+        with make_plan(case, B.HF_COPY_OWN) as pl:
+            pl.set_param(B.HF_PARAM_VARIANT, variant)
+            pl.set_param(B.HF_PARAM_MULTICAST, mc)
+            pl.set_param(B.HF_PARAM_MAX_WGS_PER_LAUNCH, 1024)
+            if variant == B.HF_VARIANT_ONE_WG_PER_TILE:
+                pl.set_param(B.HF_PARAM_TILE_BYTES, 4096)
+            assert pl.num_tiles(0) * (32 if variant == B.HF_VARIANT_PARTS else 1) > 3 * 1024
+            ar = Arena(pl)
+            ar.train.copy_(torch.from_numpy(train.view(np.int16)))
+            ar.gen.fill_(_i16(POISON))
+            ar.execute()
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want)
+
+
 def test_runtime_argument_errors():
     with make_plan(SMALL[0], 0) as pl:
         ar = Arena(pl)
