@@ -215,15 +215,20 @@ enum {
                                 stores; plain loads under HF_MULTICAST_CACHE_BLOCKED);
                                 0: both non-temporal; bit 0: plain loads; bit 1: plain
                                 stores (not for HF_VARIANT_LDS_STAGED)                   */
-  HF_PARAM_PART_BYTES = 5,   /* HF_VARIANT_PARTS: payload bytes per workgroup: 4096, 8192,
-                                16384, 32768, or 0 (default) = 8192 for the cache-blocked
-                                train->gen list and 4096 otherwise                       */
+  HF_PARAM_PART_BYTES = 5,   /* HF_VARIANT_PARTS: payload bytes per workgroup: a power of two
+                                from 4096 to 32768 (1024 to 8192 with 64-lane workgroups;
+                                values outside the range are clamped), or 0 (default) =
+                                automatic: 8192 for the cache-blocked train->gen list,
+                                1024 for plain streaming lists                           */
   HF_PARAM_MC_BLOCK_BYTES = 6, /* HF_MULTICAST_CACHE_BLOCKED: source bytes per block,
                                 1 MiB .. 1 GiB, default 2 MiB (re-tiles and re-uploads)  */
   HF_PARAM_MAX_WGS_PER_LAUNCH = 8, /* HF_VARIANT_PARTS / ONE_WG_PER_TILE: a work list that needs
                                 more workgroups goes out in several launches of at most this
                                 many, in list order; 1024 .. 16777215 (default: a HIP grid
                                 holds fewer than 2^32 threads)                            */
+  HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
+                                automatic: 256 for the cache-blocked train->gen list, 64
+                                (one wavefront) for plain streaming lists                */
   HF_PARAM_KIND_MASK = 7     /* profiling aid: bit k set = descriptors of kind k (HF_COL ..
                                 HF_GATEUP_DEINT) are executed and counted by
                                 hf_plan_bytes_moved / hf_plan_unique_src_bytes; default 31

@@ -26,7 +26,7 @@ HF_COL, HF_ROW, HF_REPL, HF_QKV_DEINT, HF_GATEUP_DEINT = range(5)
 HF_DESC_OWN, HF_DESC_ALIGN16, HF_DESC_ALIGN8, HF_DESC_ALIGN4, HF_DESC_ALIGN2 = 0x1, 0x10, 0x20, 0x40, 0x80
 HF_DIR_TRAIN_TO_GEN, HF_DIR_GEN_TO_TRAIN = 0, 1
 HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
-HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_KIND_MASK, HF_PARAM_MAX_WGS_PER_LAUNCH = 0, 1, 2, 3, 4, 5, 6, 7, 8
+HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_KIND_MASK, HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
 HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED = 0, 1, 2
 HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED, HF_VARIANT_WAVE_PERSISTENT, HF_VARIANT_PARTS = 0, 1, 2, 3, 4
 

@@ -1,6 +1,7 @@
 // C ABI of libhfreshard (declarations and contracts: include/hfreshard.h).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -97,11 +98,14 @@ int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) 
 int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *extra_dst, const void *src, void *dst,
            void *stream, bool temporal_loads = false) {
   const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : (temporal_loads ? 1 : 0);
-  // measured on the Llama-7B transition: 8 KiB per workgroup is best when later passes hit
-  // L2, 4 KiB for plain one-to-one copies
-  const uint32_t part = p.part_bytes ? (uint32_t)p.part_bytes : (temporal_loads ? 8192u : 4096u);
+  // Automatic launch shape, measured on the Llama-7B / 34B transitions: lists whose later
+  // passes hit L2 run best with 256 lanes x 2 vectors (8 KiB per workgroup); plain streaming
+  // lists with one wavefront x 1 vector (1 KiB per workgroup).
+  const int threads = p.wg_threads ? (int)p.wg_threads : (temporal_loads ? 256 : 64);
+  uint32_t part = p.part_bytes ? (uint32_t)p.part_bytes : (temporal_loads ? 8192u : threads == 64 ? 1024u : 4096u);
+  part = threads == 64 ? std::min(part, 8192u) : std::max(part, 4096u);
   const int e = hf::launch_tiles(tiles, n, extra_dst, src, dst, (int)p.variant, (int)p.grid_wgs, policy,
-                                 (uint32_t)p.tile_bytes, part, (uint32_t)p.max_wgs_per_launch, stream);
+                                 (uint32_t)p.tile_bytes, part, (uint32_t)p.max_wgs_per_launch, threads, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
@@ -194,6 +198,10 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     if (value < 1024 || value > 0xFFFFFFFFll / 256) return fail(HF_EINVAL, "workgroups per launch must be in [1024, 16777215]");
     p.max_wgs_per_launch = value;
     return HF_OK;
+  case HF_PARAM_WG_THREADS:
+    if (value != 0 && value != 64 && value != 256) return fail(HF_EINVAL, "workgroup size must be 0 (automatic), 64 or 256");
+    p.wg_threads = value;
+    return HF_OK;
   case HF_PARAM_KIND_MASK:
     if (value < 1 || value > 0x1F) return fail(HF_EINVAL, "kind mask must be in [1, 31]");
     p.kind_mask = value;
@@ -203,8 +211,8 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     p.cache_policy = value;
     return HF_OK;
   case HF_PARAM_PART_BYTES:
-    if (value != 0 && value != 4096 && value != 8192 && value != 16384 && value != 32768)
-      return fail(HF_EINVAL, "part bytes must be 0 (automatic), 4096, 8192, 16384 or 32768");
+    if (value != 0 && value != 1024 && value != 2048 && value != 4096 && value != 8192 && value != 16384 && value != 32768)
+      return fail(HF_EINVAL, "part bytes must be 0 (automatic) or a power of two from 1024 to 32768");
     p.part_bytes = value;
     return HF_OK;
   }
@@ -220,6 +228,7 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_MULTICAST: return plan->p.effective_multicast();
   case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
   case HF_PARAM_KIND_MASK: return plan->p.kind_mask;
+  case HF_PARAM_WG_THREADS: return plan->p.wg_threads;
   case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;
   case HF_PARAM_PART_BYTES: return plan->p.part_bytes;

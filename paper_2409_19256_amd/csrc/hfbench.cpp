@@ -49,7 +49,7 @@ int main(int argc, char **argv) {
       {"llama70b_gqa_tp8pp4_to_tp4", {80, 8192, 64, 8, 128, 28672, 128256, 2, 0}, {4, 8, 1}, 1, 4, {0, 31}},
   };
   int config = 2, steps = 10, warmup = 3, back = 0;
-  long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0;
+  long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0, wg_threads = 0;
   unsigned flags = HF_SKIP_OWN;
   for (int i = 1; i < argc; ++i) {
     const std::string a = argv[i];
@@ -68,10 +68,11 @@ int main(int argc, char **argv) {
     else if (a == "--cache-policy") policy = val();
     else if (a == "--calib-copy-bytes") calib = val();
     else if (a == "--kind-mask") kind_mask = val();
+    else if (a == "--wg-threads") wg_threads = val();
     else {
       std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back] [--copy-own] [--multicast 0|1|2] "
                            "[--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] [--cache-policy P] "
-                           "[--calib-copy-bytes B] [--kind-mask M]\n");
+                           "[--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256]\n");
       return 2;
     }
   }
@@ -88,6 +89,7 @@ int main(int argc, char **argv) {
   if (grid) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_GRID_WGS, grid));
   if (policy >= -1) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_CACHE_POLICY, policy));
   if (kind_mask) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_KIND_MASK, kind_mask));
+  if (wg_threads) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_WG_THREADS, wg_threads));
 
   const size_t tb = hf_plan_train_bytes(plan), gb = hf_plan_gen_bytes(plan);
   const size_t gen_start = (tb + 4095) / 4096 * 4096;

@@ -70,8 +70,9 @@ struct Plan {
   int64_t multicast = HF_MULTICAST_CACHE_BLOCKED;
   int64_t mc_block_bytes = 2 << 20;
   int64_t cache_policy = -1; // auto
-  int64_t part_bytes = 0; // 0 = chosen per launch: 8 KiB for the cache-blocked list, else 4 KiB
+  int64_t part_bytes = 0; // 0 = chosen per launch
   int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
+  int64_t wg_threads = 0; // 0 = chosen per launch
   int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (profiling aid)
 
   // device copy (null for HF_PLAN_HOST_ONLY)

@@ -143,14 +143,14 @@ __global__ __launch_bounds__(kWG) void reshard_one_tile(const hf_tile *__restric
 // window of source and destination addresses, and a slow CU simply takes fewer
 // workgroups.  kUnroll = part_bytes / 4 KiB vectors per lane, all loaded before the
 // first store.
-template <int kPolicy, int kUnroll>
-__global__ __launch_bounds__(kWG) void reshard_parts(const hf_tile *__restrict__ tiles, uint32_t n_tiles, uint32_t parts,
-                                                     const uint64_t *__restrict__ extra_dst,
-                                                     const char *__restrict__ src, char *__restrict__ dst) {
+template <int kPolicy, int kUnroll, int kThreads>
+__global__ __launch_bounds__(kThreads) void reshard_parts(const hf_tile *__restrict__ tiles, uint32_t n_tiles, uint32_t parts,
+                                                          const uint64_t *__restrict__ extra_dst,
+                                                          const char *__restrict__ src, char *__restrict__ dst) {
   const uint32_t t = blockIdx.x / parts, part = blockIdx.x - t * parts;
   if (t < n_tiles) {
     const hf_tile tl = tiles[t];
-    run_tile<kWG, kPolicy, kUnroll>(tl, extra_dst, src, dst, threadIdx.x, part, kUnroll * kWG * 16);
+    run_tile<kThreads, kPolicy, kUnroll>(tl, extra_dst, src, dst, threadIdx.x, part, kUnroll * kThreads * 16);
   }
 }
 
@@ -223,16 +223,25 @@ __global__ __launch_bounds__(kWG) void calib_write(u32x4 *__restrict__ dst, size
 
 template <int kPolicy>
 void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint64_t *extra_dst, const char *s, char *d,
-                   int variant, uint32_t tile_bytes, uint32_t part_bytes, hipStream_t st) {
+                   int variant, uint32_t tile_bytes, uint32_t part_bytes, int wg_threads, hipStream_t st) {
   switch (variant) {
   case HF_VARIANT_PARTS: {
     const uint32_t parts = (tile_bytes + part_bytes - 1) / part_bytes;
     const dim3 g(n * parts);
-    switch (part_bytes / 4096) {
-    case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-    case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-    case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-    default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    if (wg_threads == kWave) { // one wavefront per workgroup: part_bytes = U * 1 KiB
+      switch (part_bytes / 1024) {
+      case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      }
+    } else {
+      switch (part_bytes / 4096) {
+      case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+      }
     }
     break;
   }
@@ -252,7 +261,7 @@ void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint
 
 int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
                  int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes,
-                 uint32_t max_wgs_per_launch, void *stream) {
+                 uint32_t max_wgs_per_launch, int wg_threads, void *stream) {
   if (n_tiles == 0) return 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char *s = static_cast<const char *>(src);
@@ -276,10 +285,10 @@ int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_d
       hipLaunchKernelGGL(reshard_persistent_lds, dim3(grid), dim3(kWG), 0, st, t, n, extra_dst, s, d);
     } else {
       switch (cache_policy) {
-      case 1: launch_policy<1>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-      case 2: launch_policy<2>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-      case 3: launch_policy<3>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
-      default: launch_policy<0>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, st); break;
+      case 1: launch_policy<1>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
+      case 2: launch_policy<2>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
+      case 3: launch_policy<3>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
+      default: launch_policy<0>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
       }
     }
     const hipError_t e = hipGetLastError();

@@ -69,7 +69,8 @@ VARIANTS = [(B.HF_VARIANT_PERSISTENT, 128 * 1024, 2048, 1), (B.HF_VARIANT_PERSIS
             (B.HF_VARIANT_WAVE_PERSISTENT, 16 * 1024, 1024, 1), (B.HF_VARIANT_WAVE_PERSISTENT, 8192, 3, 0),
             (B.HF_VARIANT_PARTS, 32 * 1024, 4096, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 16384, 0),
             (B.HF_VARIANT_PARTS, 12288, 8192, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 4096, 2),
-            (B.HF_VARIANT_PERSISTENT, 64 * 1024, 1024, 2)]
+            (B.HF_VARIANT_PERSISTENT, 64 * 1024, 1024, 2), (B.HF_VARIANT_PARTS, 64 * 1024, -2048, 2),
+            (B.HF_VARIANT_PARTS, 16 * 1024, -1024, 1)]
 
 
 @pytest.mark.parametrize("case", SMALL + [BASELINE[0]] + MEDIUM, ids=lambda c: c["name"])
@@ -88,7 +89,8 @@ def test_whole_buffers_match_oracle(case):
         with make_plan(case, B.HF_COPY_OWN) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
             if variant == B.HF_VARIANT_PARTS:
-                pl.set_param(B.HF_PARAM_PART_BYTES, grid)      # third field = bytes per workgroup
+                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))  # third field = bytes per workgroup,
+                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)  # negative: 64-lane workgroups
             else:
                 pl.set_param(B.HF_PARAM_GRID_WGS, grid)
             pl.set_param(B.HF_PARAM_VARIANT, variant)
@@ -106,7 +108,8 @@ def test_whole_buffers_match_oracle(case):
         with make_plan(case, 0) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
             if variant == B.HF_VARIANT_PARTS:
-                pl.set_param(B.HF_PARAM_PART_BYTES, grid)      # third field = bytes per workgroup
+                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))  # third field = bytes per workgroup,
+                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)  # negative: 64-lane workgroups
             else:
                 pl.set_param(B.HF_PARAM_GRID_WGS, grid)
             pl.set_param(B.HF_PARAM_VARIANT, variant)
