@@ -224,8 +224,9 @@ enum {
                                 1 MiB .. 1 GiB, default 2 MiB (re-tiles and re-uploads)  */
   HF_PARAM_MAX_WGS_PER_LAUNCH = 8, /* HF_VARIANT_PARTS / ONE_WG_PER_TILE: a work list that needs
                                 more workgroups goes out in several launches of at most this
-                                many, in list order; 1024 .. 16777215 (default: a HIP grid
-                                holds fewer than 2^32 threads)                            */
+                                many 256-lane workgroups (four times as many 64-lane ones),
+                                in list order; 1024 .. 16777215 (default: a HIP grid holds
+                                fewer than 2^32 threads)                                  */
   HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for plain streaming lists                */

@@ -105,7 +105,8 @@ int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *ex
   uint32_t part = p.part_bytes ? (uint32_t)p.part_bytes : (temporal_loads ? 8192u : threads == 64 ? 1024u : 4096u);
   part = threads == 64 ? std::min(part, 8192u) : std::max(part, 4096u);
   const int e = hf::launch_tiles(tiles, n, extra_dst, src, dst, (int)p.variant, (int)p.grid_wgs, policy,
-                                 (uint32_t)p.tile_bytes, part, (uint32_t)p.max_wgs_per_launch, threads, stream);
+                                 (uint32_t)p.tile_bytes, part,
+                                 (uint32_t)(p.max_wgs_per_launch * (256 / threads)), threads, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
