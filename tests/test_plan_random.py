@@ -1,0 +1,79 @@
+"""Randomised host check of the planner: random shapes, layouts, flags, materialised-rank
+subsets and tuning parameters; the plan's work list, interpreted on the CPU, must give the
+oracle's buffers (whole-buffer equality incl. untouched padding / own pieces)."""
+import numpy as np
+from hypothesis import HealthCheck, given, settings, strategies as st
+
+from oracle.reshard_oracle import GenLayout, Model, ReshardOracle, TrainLayout
+from paper_2409_19256_amd import binding as B
+from tests.libcases import make_plan
+from tests.oracle_util import POISON, seeded_train_buf, source_index_map
+from tests.plan_interp import run_descs, run_tiles
+
+
+@st.composite
+def cases(draw):
+    tg = draw(st.sampled_from([1, 2, 4]))
+    a = draw(st.sampled_from([1, 2, 4]))
+    pg = draw(st.sampled_from([1, 2]))
+    b = draw(st.sampled_from([1, 2]))
+    t, p = tg * a, pg * b
+    d = draw(st.sampled_from([1, 1, 2]))
+    nkv = t * draw(st.integers(1, 2))
+    qpg = draw(st.sampled_from([1, 2, 4]))
+    hd = draw(st.sampled_from([1, 2, 3, 4, 8]))
+    hidden = draw(st.sampled_from([1, 2, 4, 6, 8, 16, 24, 136]))
+    ffn = t * draw(st.integers(1, 9))
+    vocab = t * draw(st.integers(1, 5))
+    layers = p * draw(st.integers(1, 2))
+    grouping = draw(st.sampled_from(["hybridflow", "hybridflow", "vanilla"]))
+    case = dict(model=Model(layers, hidden, nkv * qpg, nkv, hd, ffn, vocab), train=TrainLayout(p, t, d),
+                gen=GenLayout(pg, tg, grouping), name="random")
+    n = p * t * d
+    mat = draw(st.one_of(st.none(), st.lists(st.integers(0, n - 1), min_size=1, max_size=min(n, 5), unique=True)))
+    flags = draw(st.sampled_from([0, B.HF_COPY_OWN]))
+    params = dict(tile=draw(st.sampled_from([4096, 8192, 131072])), mc=draw(st.sampled_from([0, 1, 2])),
+                  block=draw(st.sampled_from([1 << 20, 2 << 20])), tiles=draw(st.booleans()))
+    return case, mat, flags, params
+
+
+@settings(max_examples=120, deadline=None, suppress_health_check=[HealthCheck.too_slow, HealthCheck.data_too_large])
+@given(cases())
+def test_random_plans_reproduce_oracle(c):
+    case, mat, flags, prm = c
+    orc = ReshardOracle(case["model"], case["train"], case["gen"])
+    ranks = list(range(orc.n_ranks)) if mat is None else mat
+    train = seeded_train_buf(orc, 31337)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    src = source_index_map(orc, ranks)
+    offs, gb = orc.train_region_offsets(), orc.gen_region_offsets(ranks)
+    written = src >= 0
+    if not flags & B.HF_COPY_OWN:
+        for i, r in enumerate(ranks):
+            reg = src[gb[i]:gb[i + 1]]
+            written[gb[i]:gb[i + 1]] &= ~((reg >= offs[r]) & (reg < offs[r + 1]))
+    with make_plan(case, B.HF_PLAN_HOST_ONLY | flags, mat=mat) as pl:
+        pl.set_param(B.HF_PARAM_TILE_BYTES, prm["tile"])
+        pl.set_param(B.HF_PARAM_MULTICAST, prm["mc"])
+        pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, prm["block"])
+        pl.validate()
+        got = np.full(want.shape, POISON, np.uint16)
+        if prm["tiles"]:
+            run_tiles(pl.tiles(0), train.view(np.uint8), got.view(np.uint8))
+        else:
+            run_descs(pl.descs(0), train.view(np.uint8), got.view(np.uint8))
+        assert np.array_equal(got[written], want[written])
+        assert (got[~written] == POISON).all()
+        assert pl.bytes_moved(0) == 2 * int(written.sum())
+        if case["gen"].grouping == "hybridflow":
+            # reverse: from complete generation buffers back to the materialised ranks' shards
+            back = np.full(train.shape, 0xBEEF, np.uint16)
+            (run_tiles if prm["tiles"] else run_descs)(pl.tiles(1) if prm["tiles"] else pl.descs(1), want.view(np.uint8),
+                                                        back.view(np.uint8))
+            for r in range(orc.n_ranks):
+                for e in orc.train_table(r)[0]:
+                    s = slice(offs[r] + e.offset, offs[r] + e.offset + e.n)
+                    if r in ranks:
+                        assert np.array_equal(back[s], train[s])
+                    else:
+                        assert (back[s] == 0xBEEF).all()
