@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--direction", default="fwd", choices=["fwd", "back"])
     ap.add_argument("--flags", default="skip_own", choices=["skip_own", "copy_own"])
+    ap.add_argument("--grouping", default="hybridflow", choices=["hybridflow", "vanilla"],
+                    help="vanilla = the paper's HybridFlow-V generation grouping (Section 5.3)")
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--grid", type=int, default=None)
@@ -133,9 +135,11 @@ def main():
         print("bench.py: no GPU visible; the reshard library has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = dict(CONFIGS[args.config], index=args.config)
-    default_config = (args.direction == "fwd" and args.flags == "skip_own" and args.variant is None and args.tile_bytes is None
+    default_config = (args.direction == "fwd" and args.flags == "skip_own" and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
                       and args.grid is None and args.multicast is None and not args.part_bytes and not args.mc_block_bytes)
     flags = B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN
+    if args.grouping == "vanilla":
+        flags |= B.HF_GROUPING_VANILLA
     t0 = time.perf_counter()
     plan = Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags, mat_ranks=cfg["mat"])
     plan_ms = (time.perf_counter() - t0) * 1e3
@@ -194,7 +198,7 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u16", "data": "synthetic",
-        "config": {"workload": cfg["name"], "direction": args.direction, "flags": args.flags,
+        "config": {"workload": cfg["name"], "direction": args.direction, "flags": args.flags, "grouping": args.grouping,
                    "ranks": plan.n_ranks, "materialised_gen_ranks": len(plan.mat_ranks), "micro_dp": plan.micro_dp_size,
                    "bytes_written": W, "unique_bytes_read": R, "arena_bytes": ar.buf.numel() * 2,
                    "tile_bytes": plan.get_param(B.HF_PARAM_TILE_BYTES), "grid_wgs": plan.get_param(B.HF_PARAM_GRID_WGS),

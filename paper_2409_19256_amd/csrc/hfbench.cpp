@@ -58,7 +58,8 @@ int main(int argc, char **argv) {
     else if (a == "--steps") steps = (int)val();
     else if (a == "--warmup") warmup = (int)val();
     else if (a == "--back") back = 1;
-    else if (a == "--copy-own") flags = HF_COPY_OWN;
+    else if (a == "--copy-own") flags |= HF_COPY_OWN;
+    else if (a == "--vanilla") flags |= HF_GROUPING_VANILLA;
     else if (a == "--multicast") multicast = val();
     else if (a == "--variant") variant = val();
     else if (a == "--tile-bytes") tile_bytes = val();
@@ -70,7 +71,7 @@ int main(int argc, char **argv) {
     else if (a == "--kind-mask") kind_mask = val();
     else if (a == "--wg-threads") wg_threads = val();
     else {
-      std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back] [--copy-own] [--multicast 0|1|2] "
+      std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back] [--copy-own] [--vanilla] [--multicast 0|1|2] "
                            "[--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] [--cache-policy P] "
                            "[--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256]\n");
       return 2;
@@ -126,11 +127,11 @@ int main(int argc, char **argv) {
     HIP_CHECK(hipStreamSynchronize(st));
     std::printf("calib_copy_bytes %zu\n", n);
   }
-  std::printf("{\"workload\": \"%s\", \"direction\": \"%s\", \"multicast\": %lld, \"variant\": %lld, \"tile_bytes\": %lld, "
+  std::printf("{\"workload\": \"%s%s\", \"direction\": \"%s\", \"multicast\": %lld, \"variant\": %lld, \"tile_bytes\": %lld, "
               "\"part_bytes\": %lld, \"mc_block_bytes\": %lld, \"bytes_written\": %zu, \"unique_bytes_read\": %zu, "
               "\"algorithmic_bytes\": %.0f, \"ms_mean\": %.4f, \"ms_median\": %.4f, \"ms_min\": %.4f, \"GBps\": %.1f, "
               "\"frac_of_8TBps\": %.4f}\n",
-              c.name, back ? "back" : "fwd", mc, (long long)hf_plan_get_param(plan, HF_PARAM_VARIANT),
+              c.name, (flags & HF_GROUPING_VANILLA) ? " (vanilla grouping)" : "", back ? "back" : "fwd", mc, (long long)hf_plan_get_param(plan, HF_PARAM_VARIANT),
               (long long)hf_plan_get_param(plan, HF_PARAM_TILE_BYTES), (long long)hf_plan_get_param(plan, HF_PARAM_PART_BYTES),
               (long long)hf_plan_get_param(plan, HF_PARAM_MC_BLOCK_BYTES), W, R, alg, mean, ms[steps / 2], ms[0], alg / mean / 1e6,
               alg / mean / 1e6 / 8000.0);
