@@ -192,6 +192,22 @@ HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *
 HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
 
+/* Section 5.2 step 3: all-gather of the generation results inside each micro-DP group.
+ * resp_in  (DEVICE, 256-byte aligned): N slots of slot_bytes; slot r holds the results
+ *          (prompt + response token ids, any 4-byte-multiple payload) that rank r's
+ *          generation replica produced for its micro-batch.
+ * resp_out (DEVICE, 256-byte aligned, not overlapping resp_in): N * d_g slots; after the
+ *          call, slots r*d_g .. r*d_g+d_g-1 hold the results of the d_g members of rank r's
+ *          micro-DP group in the order of their micro-DP index (member j = the rank
+ *          hf_plan_micro_dp_peer(plan, r, j)), i.e. every rank of a training replica ends up
+ *          with the whole batch of its micro-DP group, ready for the training stage.
+ * slot_bytes: > 0, multiple of 4; may change from call to call (the group table is part of
+ * the plan, nothing is allocated or uploaded here).  One kernel launch on hip_stream. */
+HF_API int hf_gather_responses(const hf_plan *plan, const void *resp_in, void *resp_out, size_t slot_bytes,
+                        void *hip_stream);
+/* rank with micro-DP index j (0 <= j < d_g) in the micro-DP group of `rank`; -1 if out of range */
+HF_API int hf_plan_micro_dp_peer(const hf_plan *plan, int rank, int j);
+
 /* Plain 16-byte grid-stride copy of `bytes` (multiple of 16) from src to dst (DEVICE
  * pointers, 16-byte aligned, not overlapping) on hip_stream: a kernel of known traffic,
  * for calibrating hardware counters and for measuring the copy ceiling of a box.

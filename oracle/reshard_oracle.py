@@ -544,6 +544,23 @@ class ReshardOracle:
             names += [(n, l) for n in FULL_LAYER_NAMES]
         return names + [("lnf", -1), ("head", -1)]
 
+    # ---------------------------------- step 3: all-gather of results in a micro-DP group
+    def micro_dp_members(self, r: int) -> List[int]:
+        """Ranks of r's micro-DP group, ordered by micro-DP index."""
+        dp = self.train_coords(r)[0]
+        gpp, gtp, _ = self.gen_coords(r)
+        members = [q for q in range(self.n_ranks)
+                   if self.train_coords(q)[0] == dp and self.gen_coords(q)[:2] == (gpp, gtp)]
+        return sorted(members, key=lambda q: self.gen_coords(q)[2])
+
+    def gather_responses(self, resp_in: np.ndarray) -> np.ndarray:
+        """Section 5.2 step 3.  resp_in[r] = results of rank r's generation replica (any
+        trailing shape); returns out[r] = concatenation, along a new leading axis of
+        length d_g, of the results of r's micro-DP group members in micro-DP order: what an
+        all-gather inside the group leaves on every member."""
+        assert resp_in.shape[0] == self.n_ranks
+        return np.stack([np.stack([resp_in[q] for q in self.micro_dp_members(r)]) for r in range(self.n_ranks)])
+
     # ------------------------------------------------- Table 2 closed forms (bytes)
     def model_bytes(self) -> int:
         return ELEM_BYTES * sum(int(np.prod(self.full_shape(n))) for n, _ in self.full_tensor_names())

@@ -10,6 +10,14 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhfreshard.so")
 
+# PyTorch wheels carry their own copy of the HIP runtime.  If this library pulled in the
+# system's copy first, a later `import torch` would start a second runtime that sees no
+# GPU; loading torch first makes both use the same one.  Callers without torch are fine.
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it with `python -m paper_2409_19256_amd.build` "
@@ -104,6 +112,8 @@ SIGNATURES = {
     "hf_plan_num_tiles": (C.c_size_t, [_P, C.c_int]),
     "hf_plan_get_tile": (C.c_int, [_P, C.c_int, C.c_size_t, C.POINTER(hf_tile)]),
     "hf_plan_get_tile_dst": (C.c_int, [_P, C.c_int, C.c_size_t, C.c_uint32, C.POINTER(C.c_uint64)]),
+    "hf_gather_responses": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hf_plan_micro_dp_peer": (C.c_int, [_P, C.c_int, C.c_int]),
     "hf_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hf_plan_validate": (C.c_int, [_P]),
     "hf_last_error": (C.c_char_p, []),

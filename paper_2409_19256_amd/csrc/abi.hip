@@ -33,6 +33,8 @@ void free_device(hf::Plan &p) {
   if (p.d_tiles_fwd_mc) (void)hipFree(p.d_tiles_fwd_mc);
   if (p.d_mc_dst) (void)hipFree(p.d_mc_dst);
   if (p.d_tiles_fwd_cb) (void)hipFree(p.d_tiles_fwd_cb);
+  if (p.d_micro_peers) (void)hipFree(p.d_micro_peers);
+  p.d_micro_peers = nullptr;
   p.d_tiles_fwd = p.d_tiles_back = p.d_tiles_fwd_mc = p.d_tiles_fwd_cb = nullptr;
   p.d_mc_dst = nullptr;
 }
@@ -58,6 +60,7 @@ int upload(hf::Plan &p) {
   if (rc == HF_OK) rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
   if (rc == HF_OK) rc = upload_list(p.mc_dst, &p.d_mc_dst);
   if (rc == HF_OK) rc = upload_list(p.tiles_fwd_cb, &p.d_tiles_fwd_cb);
+  if (rc == HF_OK) rc = upload_list(p.micro_peers, &p.d_micro_peers);
   if (rc != HF_OK) free_device(p);
   return rc;
 }
@@ -170,6 +173,27 @@ int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, v
   if (p.flags & HF_GROUPING_VANILLA)
     return fail(HF_EINVAL, "vanilla grouping keeps the training shard besides the generation buffer: nothing to re-partition");
   return launch(p, p.d_tiles_back, p.tiles_back.size(), nullptr, gen_buf, train_buf, hip_stream);
+}
+
+int hf_gather_responses(const hf_plan *plan, const void *resp_in, void *resp_out, size_t slot_bytes, void *hip_stream) {
+  if (!plan || !resp_in || !resp_out) return fail(HF_EINVAL, "null plan or buffer");
+  const hf::Plan &p = plan->p;
+  if (p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
+  if (slot_bytes == 0 || slot_bytes % 4) return fail(HF_EINVAL, "slot_bytes must be a positive multiple of 4");
+  if ((reinterpret_cast<uintptr_t>(resp_in) | reinterpret_cast<uintptr_t>(resp_out)) % 256)
+    return fail(HF_EINVAL, "resp_in and resp_out must be 256-byte aligned");
+  const char *a = static_cast<const char *>(resp_in), *b = static_cast<const char *>(resp_out);
+  const size_t in_bytes = (size_t)p.N * slot_bytes, out_bytes = in_bytes * p.dg;
+  if (a < b + out_bytes && b < a + in_bytes) return fail(HF_EINVAL, "resp_in and resp_out overlap");
+  const int e = hf::launch_gather_slots(p.d_micro_peers, (uint32_t)p.micro_peers.size(), resp_in, resp_out, slot_bytes, hip_stream);
+  if (e == (int)hipErrorInvalidValue) return fail(HF_ERANGE, "slots too large for one launch");
+  if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
+  return HF_OK;
+}
+
+int hf_plan_micro_dp_peer(const hf_plan *plan, int rank, int j) {
+  if (!plan || rank < 0 || rank >= plan->p.N || j < 0 || j >= plan->p.dg) return -1;
+  return plan->p.micro_peers[(size_t)rank * plan->p.dg + j];
 }
 
 int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {

@@ -49,7 +49,7 @@ int main(int argc, char **argv) {
       {"llama70b_gqa_tp8pp4_to_tp4", {80, 8192, 64, 8, 128, 28672, 128256, 2, 0}, {4, 8, 1}, 1, 4, {0, 31}},
   };
   int config = 2, steps = 10, warmup = 3, back = 0;
-  long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0, wg_threads = 0;
+  long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0, wg_threads = 0, resp_tokens = 0;
   unsigned flags = HF_SKIP_OWN;
   for (int i = 1; i < argc; ++i) {
     const std::string a = argv[i];
@@ -70,10 +70,11 @@ int main(int argc, char **argv) {
     else if (a == "--calib-copy-bytes") calib = val();
     else if (a == "--kind-mask") kind_mask = val();
     else if (a == "--wg-threads") wg_threads = val();
+    else if (a == "--responses") resp_tokens = val();
     else {
       std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back] [--copy-own] [--vanilla] [--multicast 0|1|2] "
                            "[--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] [--cache-policy P] "
-                           "[--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256]\n");
+                           "[--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--responses TOKENS_PER_REPLICA]\n");
       return 2;
     }
   }
@@ -135,6 +136,30 @@ int main(int argc, char **argv) {
               (long long)hf_plan_get_param(plan, HF_PARAM_TILE_BYTES), (long long)hf_plan_get_param(plan, HF_PARAM_PART_BYTES),
               (long long)hf_plan_get_param(plan, HF_PARAM_MC_BLOCK_BYTES), W, R, alg, mean, ms[steps / 2], ms[0], alg / mean / 1e6,
               alg / mean / 1e6 / 8000.0);
+  if (resp_tokens > 0) { // step 3: all-gather of int64 token ids inside the micro-DP groups
+    const int N = hf_plan_num_ranks(plan), dg = hf_plan_micro_dp_size(plan);
+    const size_t slot = (size_t)resp_tokens * 8;
+    char *rin = nullptr, *rout = nullptr;
+    HIP_CHECK(hipMalloc(reinterpret_cast<void **>(&rin), slot * N));
+    HIP_CHECK(hipMalloc(reinterpret_cast<void **>(&rout), slot * N * dg));
+    HIP_CHECK(hipMemset(rin, 0x22, slot * N));
+    for (int i = 0; i < 5; ++i) HF_CHECK(hf_gather_responses(plan, rin, rout, slot, st));
+    HIP_CHECK(hipStreamSynchronize(st));
+    HIP_CHECK(hipEventRecord(ev[0], st));
+    const int reps = 50;
+    for (int i = 0; i < reps; ++i) HF_CHECK(hf_gather_responses(plan, rin, rout, slot, st));
+    HIP_CHECK(hipEventRecord(ev[1], st));
+    HIP_CHECK(hipStreamSynchronize(st));
+    float t = 0;
+    HIP_CHECK(hipEventElapsedTime(&t, ev[0], ev[1]));
+    t /= reps;
+    const double bytes = 2.0 * slot * N * dg; // every output byte is written once and read once (from one of N slots)
+    std::printf("{\"step\": \"response all-gather in micro-DP groups\", \"ranks\": %d, \"micro_dp\": %d, \"slot_bytes\": %zu, "
+                "\"bytes_written\": %zu, \"ms\": %.4f, \"GBps_read_plus_write\": %.1f}\n",
+                N, dg, slot, slot * N * dg, t, bytes / t / 1e6);
+    HIP_CHECK(hipFree(rin));
+    HIP_CHECK(hipFree(rout));
+  }
   hf_plan_destroy(plan);
   HIP_CHECK(hipFree(arena));
   return 0;

@@ -17,6 +17,10 @@ namespace hf {
 int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
                  int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes,
                  uint32_t max_wgs_per_launch, int wg_threads, void *stream);
+// out slot (pair) <- in slot peers[pair] for pair in [0, n_pairs), slots of slot_bytes bytes
+// (multiple of 4).  Returns a hipError_t value.
+int launch_gather_slots(const int32_t *d_peers, uint32_t n_pairs, const void *in, void *out, size_t slot_bytes,
+                        void *stream);
 // Plain grid-stride 16-byte copy (calibration); src == null: write only, dst == null: read only.
 int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 } // namespace hf

@@ -42,6 +42,7 @@ struct Plan {
   std::vector<int> mat;     // materialised ranks in buffer order
   std::vector<int> mat_pos; // rank -> position in `mat`, -1 if absent
   std::vector<Coords> coords;
+  std::vector<int32_t> micro_peers; // [rank * dg + j] = rank with micro-DP index j in rank's micro-DP group
   std::vector<RankTable> train_tab, gen_tab; // per rank (gen_tab[r].base valid only if materialised)
   uint64_t train_bytes = 0, gen_bytes = 0;
 
@@ -82,6 +83,7 @@ struct Plan {
   hf_tile *d_tiles_fwd_mc = nullptr;
   hf_tile *d_tiles_fwd_cb = nullptr;
   uint64_t *d_mc_dst = nullptr;
+  int32_t *d_micro_peers = nullptr;
 };
 
 // Builds everything except the device copy.  Returns HF_OK or an error, with `err` set.

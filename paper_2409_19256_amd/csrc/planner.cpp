@@ -216,6 +216,16 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
     }
   }
 
+  // micro-DP groups: the d_g ranks of a replica that share (gpp, gtp), by micro-DP index
+  pl.micro_peers.assign((size_t)N * pl.dg, -1);
+  for (int r = 0; r < N; ++r)
+    for (int q = 0; q < N; ++q) {
+      const Coords &x = pl.coords[r], &y = pl.coords[q];
+      if (x.dp == y.dp && x.gpp == y.gpp && x.gtp == y.gtp) pl.micro_peers[(size_t)r * pl.dg + y.micro] = q;
+    }
+  for (int32_t q : pl.micro_peers)
+    if (q < 0) { err = "internal: incomplete micro-DP group"; return HF_EINVAL; }
+
   // ---- tensor tables -----------------------------------------------------------
   pl.train_tab.assign(N, RankTable());
   pl.gen_tab.assign(N, RankTable());

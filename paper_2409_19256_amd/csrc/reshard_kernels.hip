@@ -207,6 +207,18 @@ __global__ __launch_bounds__(kWG) void calib_copy(const u32x4 *__restrict__ src,
   for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+// All-gather of per-rank result slots inside micro-DP groups (HybridFlow Section 5.2
+// step 3): output slot `pair` receives input slot peers[pair].  One workgroup per 256
+// vectors of a slot; the slots are small (token ids), so this is launch/latency bound.
+template <typename V>
+__global__ __launch_bounds__(kWG) void gather_slots(const int32_t *__restrict__ peers, uint32_t n_pairs, uint32_t chunks,
+                                                    uint64_t slot_vecs, const V *__restrict__ in, V *__restrict__ out) {
+  const uint32_t pair = blockIdx.x / chunks, chunk = blockIdx.x - pair * chunks;
+  if (pair >= n_pairs) return;
+  const uint64_t i = (uint64_t)chunk * kWG + threadIdx.x;
+  if (i < slot_vecs) out[(uint64_t)pair * slot_vecs + i] = in[(uint64_t)peers[pair] * slot_vecs + i];
+}
+
 // read-only and write-only counterparts of calib_copy (ceilings of one direction)
 __global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec, uint32_t *__restrict__ sink) {
   const size_t stride = (size_t)gridDim.x * kWG;
@@ -295,6 +307,23 @@ int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_d
     if (e != hipSuccess) return (int)e;
   }
   return 0;
+}
+
+int launch_gather_slots(const int32_t *d_peers, uint32_t n_pairs, const void *in, void *out, size_t slot_bytes,
+                        void *stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool wide = slot_bytes % 16 == 0;
+  const uint64_t slot_vecs = slot_bytes / (wide ? 16 : 4);
+  const uint64_t chunks = (slot_vecs + kWG - 1) / kWG;
+  if (chunks * n_pairs > 0xFFFFFFFFull / kWG) return (int)hipErrorInvalidValue; // beyond one HIP grid
+  const dim3 grid((uint32_t)(chunks * n_pairs));
+  if (wide)
+    hipLaunchKernelGGL(gather_slots<u32x4>, grid, dim3(kWG), 0, st, d_peers, n_pairs, (uint32_t)chunks, slot_vecs,
+                       static_cast<const u32x4 *>(in), static_cast<u32x4 *>(out));
+  else
+    hipLaunchKernelGGL(gather_slots<uint32_t>, grid, dim3(kWG), 0, st, d_peers, n_pairs, (uint32_t)chunks, slot_vecs,
+                       static_cast<const uint32_t *>(in), static_cast<uint32_t *>(out));
+  return (int)hipGetLastError();
 }
 
 int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {

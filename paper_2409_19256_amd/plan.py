@@ -53,6 +53,12 @@ class Plan:
     def install_own(self, train_ptr: int, gen_ptr: int, stream: int = 0):
         B.check(B.hf_reshard_install_own(self._h, train_ptr, gen_ptr, stream), "hf_reshard_install_own")
 
+    def gather_responses(self, in_ptr: int, out_ptr: int, slot_bytes: int, stream: int = 0):
+        B.check(B.hf_gather_responses(self._h, in_ptr, out_ptr, slot_bytes, stream), "hf_gather_responses")
+
+    def micro_dp_peers(self, rank: int) -> List[int]:
+        return [B.hf_plan_micro_dp_peer(self._h, rank, j) for j in range(self.micro_dp_size)]
+
     def set_param(self, param: int, value: int):
         B.check(B.hf_plan_set_param(self._h, param, value), "hf_plan_set_param")
 
