@@ -92,6 +92,9 @@ int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) 
   if (plan->p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
   if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
     return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->p.device)
+    return fail(HF_EINVAL, "the current HIP device is not the one the plan was built on");
   const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
   if (t0 < g0 + plan->p.gen_bytes && g0 < t0 + plan->p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
   return HF_OK;

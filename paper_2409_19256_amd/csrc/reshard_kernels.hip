@@ -220,12 +220,14 @@ __global__ __launch_bounds__(kWG) void gather_slots(const int32_t *__restrict__ 
 }
 
 // read-only and write-only counterparts of calib_copy (ceilings of one direction)
-__global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec, uint32_t *__restrict__ sink) {
+__device__ uint32_t calib_sink; // only ever written by calib_read, never read
+__global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec) {
   const size_t stride = (size_t)gridDim.x * kWG;
   u32x4 acc = {0, 0, 0, 0};
   for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
-  // data dependent, practically never true: keeps the loads alive without a store stream
-  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;
+  // data dependent and rare: keeps the loads alive without a store stream; the caller's
+  // buffers are never written
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) calib_sink = acc.x;
 }
 __global__ __launch_bounds__(kWG) void calib_write(u32x4 *__restrict__ dst, size_t n_vec) {
   const size_t stride = (size_t)gridDim.x * kWG;
@@ -331,9 +333,8 @@ int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (src && dst)
     hipLaunchKernelGGL(calib_copy, dim3(4096), dim3(kWG), 0, st, static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), bytes / 16);
-  else if (src) // read only; the first 4 bytes of src double as the (never written) sink
-    hipLaunchKernelGGL(calib_read, dim3(4096), dim3(kWG), 0, st, static_cast<const u32x4 *>(src), bytes / 16,
-                       reinterpret_cast<uint32_t *>(const_cast<void *>(src)));
+  else if (src) // read only
+    hipLaunchKernelGGL(calib_read, dim3(4096), dim3(kWG), 0, st, static_cast<const u32x4 *>(src), bytes / 16);
   else
     hipLaunchKernelGGL(calib_write, dim3(4096), dim3(kWG), 0, st, static_cast<u32x4 *>(dst), bytes / 16);
   return (int)hipGetLastError();

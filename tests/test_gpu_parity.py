@@ -239,6 +239,40 @@ def test_work_lists_longer_than_one_grid_are_split_into_launches():
             assert np.array_equal(_d2h(ar.gen), want)
 
 
+def test_execute_and_back_can_be_captured_in_a_hip_graph():
+    """The entry points only enqueue kernels on the given stream (no allocation, no memset,
+    no synchronisation), so a caller may capture them.  Every replay is checked, with eager
+    work and synchronisation between replays."""
+    case = SMALL[3]
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    with make_plan(case, B.HF_COPY_OWN) as pl:
+        ar = Arena(pl)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()                       # default priority
+        ar.train.zero_()
+        ar.gen.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            ar.execute()                                 # warm-up outside capture
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            ar.execute()                                 # Arena passes the capturing stream
+        for k in range(4):
+            train = seeded_train_buf(orc, 100 + k)
+            want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+            ar.train.copy_(torch.from_numpy(train.view(np.int16)))
+            ar.gen.fill_(_i16(POISON))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want), f"replay {k}"
+            ar.gen.fill_(_i16(POISON))                   # eager launch of the same call in between
+            ar.execute()
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want)
+
+
 def test_runtime_argument_errors():
     with make_plan(SMALL[0], 0) as pl:
         ar = Arena(pl)
