@@ -288,12 +288,14 @@ def _device_fetch(train_i16):
     return fetch
 
 
-def _check_full_size(case, cfg_index, sampled_layers, n_elem_samples=400, check_back=False):
+def _check_full_size(case, cfg_index, sampled_layers, n_elem_samples=400, check_back=False, params=()):
     orc = make_oracle(case)
     ranks = mat_ranks(case, orc)
     seed = config_seed(cfg_index)
     rng = np.random.default_rng(cfg_index)
     with make_plan(case, 0) as pl:                         # bench.py's configuration: SKIP_OWN, defaults
+        for k, v in params:
+            pl.set_param(k, v)
         ar = Arena(pl)
         _say(f"[{case['name']}] arena {ar.buf.numel() * 2 / 1e9:.1f} GB, W = {pl.bytes_moved(0) / 1e9:.2f} GB; filling inputs")
         ar.train.fill_(_i16(POISON))
@@ -384,6 +386,16 @@ def _check_full_size(case, cfg_index, sampled_layers, n_elem_samples=400, check_
 
 def test_llama7b_full_size():
     _check_full_size(BASELINE[1], 1, [(0, 0), (5, 17), (7, 31), (3, -1)], check_back=True)
+
+
+@pytest.mark.parametrize("mode", [B.HF_MULTICAST_OFF, B.HF_MULTICAST_REGISTERS])
+def test_llama7b_full_size_other_multicast_modes(mode):
+    _check_full_size(BASELINE[1], 1, [(2, 9)], n_elem_samples=200, params=[(B.HF_PARAM_MULTICAST, mode)])
+
+
+def test_llama7b_full_size_persistent_wavefront_kernel():
+    _check_full_size(BASELINE[1], 1, [(6, 30)], n_elem_samples=200,
+                     params=[(B.HF_PARAM_VARIANT, B.HF_VARIANT_WAVE_PERSISTENT), (B.HF_PARAM_TILE_BYTES, 16384)])
 
 
 def test_llama13b_full_size_with_reverse():
