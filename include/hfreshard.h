@@ -227,10 +227,13 @@ enum {
                                 of the plan has more than one destination (e.g. only one
                                 rank per micro-DP group is materialised) every mode runs
                                 as HF_MULTICAST_OFF, and hf_plan_get_param says so.      */
-  HF_PARAM_CACHE_POLICY = 4, /* -1 (default): chosen by the library (non-temporal loads and
-                                stores; plain loads under HF_MULTICAST_CACHE_BLOCKED);
-                                0: both non-temporal; bit 0: plain loads; bit 1: plain
-                                stores (not for HF_VARIANT_LDS_STAGED)                   */
+  HF_PARAM_CACHE_POLICY = 4, /* -1 (default): chosen by the library (0 for one-to-one
+                                streaming lists, 5 for the cache-blocked list, 4 for
+                                multi-destination tiles); 0 = non-temporal loads and
+                                system-scope streaming stores; bit 0 = plain loads,
+                                bit 1 = plain stores, 4 / 5 = compiler non-temporal stores
+                                with non-temporal / plain loads (not for
+                                HF_VARIANT_LDS_STAGED)                                   */
   HF_PARAM_PART_BYTES = 5,   /* HF_VARIANT_PARTS: payload bytes per workgroup: a power of two
                                 from 4096 to 32768 (1024 to 8192 with 64-lane workgroups;
                                 values outside the range are clamped), or 0 (default) =

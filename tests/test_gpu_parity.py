@@ -194,7 +194,7 @@ def test_cache_policies_and_calibration_copies():
     with make_plan(case, B.HF_COPY_OWN) as pl:
         ar = Arena(pl)
         ar.train.copy_(torch.from_numpy(train.view(np.int16)))
-        for policy in (1, 2, 3):
+        for policy in (0, 1, 2, 3, 4, 5):
             pl.set_param(B.HF_PARAM_CACHE_POLICY, policy)
             ar.gen.fill_(_i16(POISON))
             ar.execute()

@@ -331,7 +331,7 @@ def test_error_codes():
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_MULTICAST, 3)
         with pytest.raises(B.HfError):
-            pl.set_param(B.HF_PARAM_CACHE_POLICY, 4)
+            pl.set_param(B.HF_PARAM_CACHE_POLICY, 6)
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_PART_BYTES, 12288)
         with pytest.raises(B.HfError):
