@@ -40,7 +40,8 @@ concatenated in rank order (generation: in the order of the materialised ranks).
 
 parity pins: tests/test_oracle_*.py (paper's Figure 8 worked example, Table 2 closed
 forms, brute-force element maps, round trip, overlap invariant, library-concat
-special cases).  The fused-QKV group order, the gate/up order and the stage that owns
+special cases; the offload image by brute force over single elements, the Table 2
+volume and hand-worked offsets).  The fused-QKV group order, the gate/up order and the stage that owns
 embed/head are conventions of this repository, not of the paper: for them parity is
 "unpinned by the paper" and pinned only by the hand-written fixtures in tests/golden.
 """
@@ -560,6 +561,66 @@ class ReshardOracle:
         all-gather inside the group leaves on every member."""
         assert resp_in.shape[0] == self.n_ranks
         return np.stack([np.stack([resp_in[q] for q in self.micro_dp_members(r)]) for r in range(self.n_ranks)])
+
+    # ---------------------- offload image of the remote pieces (Section 7, "Implementation")
+    # The generation copy of the weights leaves the GPU while the model trains.  What a
+    # rank has to move is what the transition gathered for it: the elements of its
+    # generation partition that do not come from its own training shard (Section 5.3: the
+    # own shard is reused in place).  Reading of this repository (the paper gives no
+    # format): the image lists, for every materialised rank in buffer order and every
+    # generation tensor in table order, the remote elements in row-major order; a rank's
+    # part starts at a multiple of RANK_ALIGN bytes, a tensor's part at a multiple of
+    # TENSOR_ALIGN bytes, tensors without remote elements take no space.
+    def owner_tags(self, mat_ranks: Sequence[int]) -> np.ndarray:
+        """gen_buf-shaped int32 array: the rank whose training shard supplies each element
+        (-1 for padding), obtained by pushing rank tags through the concat/slice code."""
+        offs = self.train_region_offsets()
+        tags = np.empty(offs[-1], dtype=np.int32)
+        for q in range(self.n_ranks):
+            tags[offs[q]:offs[q + 1]] = q
+        saved, self.check_replicas = self.check_replicas, False   # norm copies carry different tags
+        try:
+            return self.reshard(tags, np.full(self.gen_region_offsets(mat_ranks)[-1], -1, dtype=np.int32), mat_ranks)
+        finally:
+            self.check_replicas = saved
+
+    def remote_layout(self, mat_ranks: Sequence[int]):
+        """(parts, rank_offsets, total): parts = [(rank, Entry, image element offset, mask)]
+        with mask = bool array over the tensor's elements (row-major), True = remote."""
+        tags = self.owner_tags(mat_ranks)
+        bases = self.gen_region_offsets(mat_ranks)
+        parts, rank_offsets, off = [], [], 0
+        for i, r in enumerate(mat_ranks):
+            off = _round_up(off, RANK_ALIGN // ELEM_BYTES)
+            rank_offsets.append(off)
+            for e in self.gen_table(r)[0]:
+                mask = tags[bases[i] + e.offset: bases[i] + e.offset + e.n] != r
+                n = int(mask.sum())
+                if n == 0:
+                    continue
+                off = _round_up(off, TENSOR_ALIGN // ELEM_BYTES)
+                parts.append((r, e, off, mask))
+                off += n
+        return parts, rank_offsets, _round_up(off, RANK_ALIGN // ELEM_BYTES)
+
+    def pack_remote(self, gen_buf: np.ndarray, mat_ranks: Sequence[int], image: np.ndarray) -> np.ndarray:
+        """Offload: copy the remote elements of gen_buf into `image` (gaps left as they are)."""
+        parts, _, total = self.remote_layout(mat_ranks)
+        assert image.shape[0] >= total
+        bases = dict(zip(mat_ranks, self.gen_region_offsets(mat_ranks)))
+        for r, e, off, mask in parts:
+            vals = gen_buf[bases[r] + e.offset: bases[r] + e.offset + e.n][mask]
+            image[off:off + vals.shape[0]] = vals
+        return image
+
+    def unpack_remote(self, image: np.ndarray, gen_buf: np.ndarray, mat_ranks: Sequence[int]) -> np.ndarray:
+        """Reload: put the image's elements back; own pieces and padding are not written."""
+        parts, _, _ = self.remote_layout(mat_ranks)
+        bases = dict(zip(mat_ranks, self.gen_region_offsets(mat_ranks)))
+        for r, e, off, mask in parts:
+            view = gen_buf[bases[r] + e.offset: bases[r] + e.offset + e.n]
+            view[mask] = image[off:off + int(mask.sum())]
+        return gen_buf
 
     # ------------------------------------------------- Table 2 closed forms (bytes)
     def model_bytes(self) -> int:
