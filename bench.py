@@ -5,7 +5,7 @@ ranks of the workload, inputs resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--direction fwd|back]
                     [--flags skip_own|copy_own] [--variant V] [--tile-bytes B] [--grid G]
-                    [--no-cpu-baseline]
+                    [--no-cpu-baseline] [--no-ceilings] [--no-full-refresh]
 """
 import argparse
 import json
@@ -33,24 +33,32 @@ CONFIGS = {
 }
 
 
-def measured_traffic(workload, default_config):
-    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload (a
-    separate profiling run of the same launch configuration); None if there is none or if
-    this run does not use the default configuration the counters were taken with."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+def measured_traffic(workload, direction, default_config):
+    """(HBM bytes per launch, source) from the committed rocprofv3 counter summary of this
+    workload and direction (a separate profiling run of the same launch configuration: it is
+    NOT measured in this process); (None, None) if there is none or if this run does not use
+    the default configuration the counters were taken with."""
+    name = f"hbm_traffic_{workload}{'_back' if direction == 'back' else ''}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     if not default_config or not os.path.exists(path):
-        return None
+        return None, None
     vals = {}
     for line in open(path):
         if "=" in line and not line.startswith("#"):
             k, v = line.split("=")
             vals[k.strip()] = int(v)
-    return vals.get("fetch_bytes_per_launch", 0) + vals.get("write_bytes_per_launch", 0) or None
+    total = vals.get("fetch_bytes_per_launch", 0) + vals.get("write_bytes_per_launch", 0)
+    return (total or None), f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run, replayed here)"
 
 
-def cpu_baseline(cfg, alg_per_written_byte, seconds_target=15.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: whole
-    layers of all materialised generation ranks until about `seconds_target` s are spent."""
+def cpu_baseline(cfg, seconds_target=9.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: whole layers
+    of all materialised generation ranks, first on one thread, then (further layers) with a
+    plain thread pool over (rank, tensor) on all cores the process may use.  Bytes are
+    counted as for the GPU figure of a full refresh: every generation byte the oracle writes
+    plus every distinct training byte it reads."""
+    from concurrent.futures import ThreadPoolExecutor
+
     import numpy as np
 
     from oracle.reshard_oracle import GenLayout, Model, ReshardOracle, TrainLayout
@@ -62,10 +70,13 @@ def cpu_baseline(cfg, alg_per_written_byte, seconds_target=15.0):
     ranks = cfg["mat"] if cfg["mat"] is not None else list(range(orc.n_ranks))
     seed = config_seed(cfg["index"] - 1)
     offs = orc.train_region_offsets()
-    spent, moved, layers_done = 0.0, 0, 0
-    for layer in range(orc.m.n_layers):
-        # inputs of this layer for every training rank (not timed)
-        store = {}
+    cores = len(os.sched_getaffinity(0))
+    for r in range(orc.n_ranks):                      # table caches, so that threads only read them
+        e0 = orc.train_table(r)[0][0]
+        orc.train_entry(r, e0.kind, e0.layer)
+
+    def layer_inputs(layer):                          # not timed
+        store, n = {}, 0
         for r in range(orc.n_ranks):
             _, pp, tp = orc.train_coords(r)
             if layer // orc.lps != pp:
@@ -74,29 +85,91 @@ def cpu_baseline(cfg, alg_per_written_byte, seconds_target=15.0):
                 if e.layer == layer:
                     uid = tensor_uid(e.kind, layer, 0 if e.kind in ("ln1", "ln2") else tp)
                     store[offs[r] + e.offset] = bits16_torch(stream_key(seed, uid), 0, e.n).numpy().view(np.uint16)
-        fetch = lambda o, n: store[o]
-        t0 = time.perf_counter()
-        for r in ranks:
-            own = {(e.kind, e.layer) for e in orc.train_table(r)[0]}
-            for e in orc.gen_table(r)[0]:
-                if e.layer != layer:
-                    continue
-                out = orc.gen_tensor(fetch, r, e.kind, e.layer)
-                out = np.ascontiguousarray(out)      # the write into the generation buffer
-                # bytes the GPU path moves for this tensor: everything but the own training piece
-                own_n = 0
-                if layer // orc.lps == orc.train_coords(r)[1]:
-                    own_n = e.n // orc.a if e.kind not in ("ln1", "ln2") else e.n
-                moved += 2 * (e.n - own_n)
-        spent += time.perf_counter() - t0
-        layers_done += 1
-        if spent >= seconds_target:
-            break
-    alg = alg_per_written_byte * moved       # same byte accounting as the GPU figure
-    return {"value": round(alg / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"oracle (rebuild full tensors from all shards, slice) on layers 0..{layers_done - 1} of {orc.m.n_layers} for all "
-                      f"{len(ranks)} generation ranks of {cfg['name']}: {moved / 1e9:.2f} GB of remote pieces produced, "
-                      f"{alg / 1e9:.2f} GB by the GPU figure's read+write accounting, in {spent:.1f} s; numpy, 1 thread"}
+                    n += e.n
+        return store, 2 * n
+
+    def one(fetch, r, e):
+        out = np.ascontiguousarray(orc.gen_tensor(fetch, r, e.kind, e.layer))     # the write into the generation buffer
+        return 2 * out.size
+
+    # one layer's inputs are generated once (seeded, not timed) and that layer is resharded again
+    # and again: every layer of the model has the same shapes, and the oracle never looks at values
+    layer = orc.m.n_layers // 2
+    store, in_bytes = layer_inputs(layer)
+    fetch = lambda o, n: store[o]
+    work = [(r, e) for r in ranks for e in orc.gen_table(r)[0] if e.layer == layer]
+    legs = []
+    for threads in sorted({1, cores}):
+        spent, written, read, reps = 0.0, 0, 0, 0
+        pool = ThreadPoolExecutor(threads) if threads > 1 else None
+        while spent < seconds_target:
+            t0 = time.perf_counter()
+            if pool:
+                written += sum(pool.map(lambda re: one(fetch, *re), work))
+            else:
+                written += sum(one(fetch, r, e) for r, e in work)
+            spent += time.perf_counter() - t0
+            read += in_bytes
+            reps += 1
+        if pool:
+            pool.shutdown()
+        legs.append({"value": round((written + read) / spent / 1e9, 3), "cores": threads, "reps": reps,
+                     "seconds": round(spent, 1), "GB": round((written + read) / 1e9, 2)})
+    best = legs[-1]
+    return {"value": best["value"], "unit": "GB/s", "cores": best["cores"], "kind": "oracle",
+            "single_thread": {"value": legs[0]["value"], "unit": "GB/s", "cores": 1},
+            "sample": f"numpy oracle (rebuild every full tensor from all training shards, slice): layer {layer} of {orc.m.n_layers} (all layers "
+                      f"have the same shapes) for all {len(ranks)} generation ranks of {cfg['name']}, repeated: {legs[0]['reps']} times on 1 thread "
+                      f"({legs[0]['GB']} GB in {legs[0]['seconds']} s)"
+                      + (f", {best['reps']} times on a pool of {best['cores']} threads over (rank, tensor) ({best['GB']} GB in {best['seconds']} s)"
+                         if len(legs) > 1 else "")
+                      + "; bytes = generation bytes written + distinct training bytes read (the accounting of the GPU's full refresh)"}
+
+
+def measured_ceilings(ar, n_dst, stream):
+    """What this machine sustains for plain streams of known traffic, from the library's
+    calibration kernels, in this process after the timed region: one-shot workgroups like the
+    default kernel, a read-only, a write-only and a 1:1 stream, and the workload's own mix of
+    one read per n_dst writes (loaded once and stored n_dst times, or copied block-wise so
+    that L2 serves the re-reads).  The copies scribble over gen_buf."""
+    import torch
+
+    from paper_2409_19256_amd import binding as B
+
+    src_bytes = min(4 << 30, ar.train.numel() * 2, ar.gen.numel() * 2 // max(n_dst, 1)) // 65536 * 65536
+    region = ar.gen.numel() * 2 // max(len(ar.plan.mat_ranks), 1) // 256 * 256
+    stride = region if region >= src_bytes and (n_dst - 1) * region + src_bytes <= ar.gen.numel() * 2 else src_bytes
+
+    def timed(fn, traffic, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return round(traffic / (a.elapsed_time(b) / reps * 1e-3) / 1e9, 1)
+
+    def fan(src, dst, n, blk, wg):
+        return lambda: B.check(B.hf_calib_fanout(src, dst, src_bytes, n, stride if n > 1 else src_bytes, blk, wg, stream), "hf_calib_fanout")
+
+    t, g = ar.train_ptr, ar.gen_ptr
+    out = {"unit": "GB/s", "source_bytes": src_bytes,
+           "read_only": timed(fan(t, None, 1, 0, 1024), src_bytes),
+           "write_only": timed(fan(None, g, 1, 0, 1024), src_bytes),
+           "copy_1_to_1": max(timed(fan(t, g, 1, 0, wg), 2 * src_bytes) for wg in (1024, 4096))}
+    if n_dst > 1:
+        mix = {f"registers_{wg}B": timed(fan(t, g, n_dst, 0, wg), (1 + n_dst) * src_bytes) for wg in (1024, 4096)}
+        mix.update({f"cache_blocked_{blk >> 20}MiB_{wg}B": timed(fan(t, g, n_dst, blk, wg), (1 + n_dst) * src_bytes)
+                    for blk in (2 << 20, 4 << 20) for wg in (4096, 8192)})
+        out["mix"] = f"1 read : {n_dst} writes, destinations {stride} bytes apart"
+        out["mix_variants"] = mix
+        out["mix_best"] = max(mix.values())
+    else:
+        out["mix"] = "1 read : 1 write"
+        out["mix_best"] = out["copy_1_to_1"]
+    return out
 
 
 def main():
@@ -116,6 +189,8 @@ def main():
     ap.add_argument("--part-bytes", type=int, default=None)
     ap.add_argument("--mc-block-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration streams after the timed region")
+    ap.add_argument("--no-full-refresh", action="store_true", help="skip the HF_COPY_OWN leg after the timed region")
     ap.add_argument("--calib-copy-bytes", type=int, default=0,
                     help="after the timed region, launch the library's plain copy kernel once over this many bytes "
                          "(a dispatch of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -135,7 +210,7 @@ def main():
         print("bench.py: no GPU visible; the reshard library has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = dict(CONFIGS[args.config], index=args.config)
-    default_config = (args.direction == "fwd" and args.flags == "skip_own" and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
+    default_config = (args.flags == "skip_own" and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
                       and args.grid is None and args.multicast is None and not args.part_bytes and not args.mc_block_bytes)
     flags = B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN
     if args.grouping == "vanilla":
@@ -185,14 +260,44 @@ def main():
     # piece to every rank that wants it (then the smaller, distinct-bytes figure counts)
     multicast = plan.get_param(B.HF_PARAM_MULTICAST) if args.direction == "fwd" else 0
     alg_bytes = W + (R if multicast else W)
+    value = alg_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+
+    # The transition a caller pays per RLHF iteration when the trainer updates train_buf (and
+    # not the own view inside gen_buf): the own pieces must be refreshed too.  One launch of a
+    # HF_COPY_OWN plan rewrites every byte of every generation buffer.
+    full_refresh = None
+    if args.direction == "fwd" and args.flags == "skip_own" and not args.no_full_refresh:
+        with Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags | B.HF_COPY_OWN, mat_ranks=cfg["mat"]) as pc:
+            for k, v in ((B.HF_PARAM_MULTICAST, args.multicast), (B.HF_PARAM_PART_BYTES, args.part_bytes),
+                         (B.HF_PARAM_MC_BLOCK_BYTES, args.mc_block_bytes), (B.HF_PARAM_TILE_BYTES, args.tile_bytes)):
+                if v:
+                    pc.set_param(k, v)
+            st = ar.stream_handle()
+            for _ in range(3):
+                pc.execute(ar.train_ptr, ar.gen_ptr, st)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+            for a, b in evs:
+                a.record()
+                pc.execute(ar.train_ptr, ar.gen_ptr, st)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+            Wc, Rc = pc.bytes_moved(0), pc.unique_src_bytes(0)
+            algc = Wc + (Rc if pc.get_param(B.HF_PARAM_MULTICAST) else Wc)
+            full_refresh = {"what": "one hf_reshard_execute of a HF_COPY_OWN plan: own pieces rewritten too (needed when the trainer "
+                                    "updates train_buf rather than the own view inside gen_buf)",
+                            "ms": round(ms, 4), "bytes_written": Wc, "unique_bytes_read": Rc,
+                            "GBps": round(algc / (ms * 1e-3) / 1e9, 1), "frac_of_peak": round(algc / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    ceilings = None
+    if not args.no_ceilings and cfg["name"] != "tiny":
+        ceilings = measured_ceilings(ar, max(1, round(W / R)) if multicast else 1, ar.stream_handle())
     if args.calib_copy_bytes:
         n = min(args.calib_copy_bytes, ar.gen.numel()) // 16 * 16
         B.check(B.hf_calib_copy(ar.train_ptr, ar.gen_ptr, min(n, ar.train.numel() * 2 // 16 * 16), ar.stream_handle()), "hf_calib_copy")
         torch.cuda.synchronize()
-        ar.install_own()   # the calibration copy scribbled over gen_buf; nothing after this reads it
-        torch.cuda.synchronize()
-    value = alg_bytes / (ms_per_step * 1e-3) / 1e9
-    achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    traffic, traffic_source = measured_traffic(cfg["name"], args.direction, default_config)
     out = {
         "metric": "reshard GB/s (read+write), train->gen transition" if args.direction == "fwd" else "reshard GB/s (read+write), gen->train",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -212,16 +317,19 @@ def main():
         "plan_build_upload_ms": round(plan_ms, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(cfg["name"], default_config),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": ["reshard_persistent", "reshard_one_tile", "reshard_persistent_lds", "reshard_wave_persistent",
                                 "reshard_parts"][plan.get_param(B.HF_PARAM_VARIANT)],
                      "algorithmic_bytes_per_launch": alg_bytes,
-                     "avg_kernel_ms": round(avg_kernel_ms, 4)},
+                     "avg_kernel_ms": round(avg_kernel_ms, 4),
+                     "measured_ceiling": ceilings,
+                     "frac_of_measured_mix_ceiling": round(achieved / ceilings["mix_best"], 4) if ceilings else None},
+        "transition_full_refresh": full_refresh,
     }
     if not args.no_cpu_baseline:
         del ar
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(cfg, alg_bytes / W)
+        out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out), flush=True)
 
 

@@ -80,6 +80,8 @@ typedef struct {
 #define HF_PLAN_HOST_ONLY 0x4u   /* build no device copy of the plan: every query works,
                                     execute/back/install return HF_EINVAL.  For hosts
                                     without a GPU.                                      */
+#define HF_PLAN_OFFLOAD 0x8u     /* also build (and upload) the work lists of
+                                    hf_offload_remote / hf_reload_remote                */
 
 /* Generation sizes p_g-t_g (Section 5.1); the micro-DP size is derived,
  * d_g = p*t/(p_g*t_g).  mat_ranks (host pointer, copied) lists the ranks whose
@@ -156,6 +158,8 @@ typedef struct {
 
 #define HF_DIR_TRAIN_TO_GEN 0
 #define HF_DIR_GEN_TO_TRAIN 1
+#define HF_DIR_OFFLOAD 2 /* gen_buf -> packed host image of the remote pieces */
+#define HF_DIR_RELOAD 3  /* packed host image -> gen_buf                      */
 #define HF_BUF_TRAIN 0
 #define HF_BUF_GEN 1
 
@@ -186,8 +190,18 @@ HF_API void hf_plan_destroy(hf_plan *plan);
  *   materialised rank from that rank's own generation buffer.  HF_EINVAL for a plan
  *   with HF_GROUPING_VANILLA, where the training shard is not inside the generation
  *   buffer (Section 5.3) and has to be kept besides it instead.
- * hf_reshard_install_own: copies only the own pieces train_buf[r] -> gen_buf[r]; the
- *   one-time placement that makes HF_SKIP_OWN's residency assumption true. */
+ * hf_reshard_install_own: copies only the own pieces train_buf[r] -> gen_buf[r]: what
+ *   makes HF_SKIP_OWN's residency assumption true.
+ *
+ * Freshness contract.  train_buf and gen_buf are separate memory, so under HF_SKIP_OWN
+ * the own pieces inside gen_buf[r] are as old as the last hf_reshard_install_own (or the
+ * last write of the caller through the own view, hf_plan_get_own_view, which is where a
+ * trainer that updates the weights in place inside the generation buffer keeps them).  A
+ * caller that updates train_buf instead must refresh the own pieces after every update:
+ * either hf_reshard_execute + hf_reshard_install_own on a HF_SKIP_OWN plan, or one
+ * hf_reshard_execute on a HF_COPY_OWN plan (one launch, every byte of every generation
+ * buffer rewritten).  hf_reshard_execute alone on a HF_SKIP_OWN plan moves exactly the
+ * bytes the paper's all-gather moves between GPUs (Section 5.4) and nothing else. */
 HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
@@ -208,15 +222,59 @@ HF_API int hf_gather_responses(const hf_plan *plan, const void *resp_in, void *r
 /* rank with micro-DP index j (0 <= j < d_g) in the micro-DP group of `rank`; -1 if out of range */
 HF_API int hf_plan_micro_dp_peer(const hf_plan *plan, int rank, int j);
 
+/* ---- offload / reload of the remote pieces (Section 7, "Implementation": the weights of
+ * the generation stage are kept in a buffer of their own, moved to host memory while the
+ * model trains and brought back in the transition).  What leaves the GPU is exactly what
+ * the transition gathered: the pieces of the d_g-1 micro-DP peers in every materialised
+ * generation buffer; the own pieces (the training shard, Section 5.3) stay.
+ * host_buf: PINNED host memory that the device can address (hipHostMalloc; torch's
+ *   pin_memory), 256-byte aligned, at least hf_plan_remote_bytes long.  Packed image: for
+ *   every materialised rank in buffer order (part starts rounded up to 4096 B; see
+ *   hf_plan_remote_rank_offset), for every generation tensor in table order that has
+ *   remote elements (tensor parts rounded up to 256 B): its remote elements in row-major
+ *   order.  Bytes between the parts are never written.
+ * Both calls need a plan built with HF_PLAN_OFFLOAD; they enqueue one kernel on hip_stream
+ * that reads / writes host_buf across the host link, and never allocate or synchronise.
+ * hf_offload_remote leaves gen_buf as it is (the caller may then reuse the remote parts);
+ * hf_reload_remote writes only remote pieces: own pieces and padding are left alone.
+ * HF_EINVAL if host_buf is not pinned host memory. */
+HF_API int hf_offload_remote(const hf_plan *plan, const void *gen_buf, void *host_buf, void *hip_stream);
+HF_API int hf_reload_remote(const hf_plan *plan, const void *host_buf, void *gen_buf, void *hip_stream);
+HF_API size_t hf_plan_remote_bytes(const hf_plan *plan);                /* size of the packed image */
+HF_API size_t hf_plan_remote_rank_offset(const hf_plan *plan, int rank); /* (size_t)-1 if not mat.  */
+
+/* Host-side check of a caller's buffers against the plan, for set-up code (not needed on
+ * the hot path): HF_EINVAL if a pointer is null or not 256-byte aligned, if the ranges
+ * overlap, or if train_len / gen_len (bytes the caller owns from the pointers on) are
+ * smaller than hf_plan_train_bytes / hf_plan_gen_bytes.  With a device plan the ranges
+ * must also lie inside device allocations of the HIP runtime (HF_ERANGE otherwise). */
+HF_API int hf_plan_check_buffers(const hf_plan *plan, const void *train_buf, size_t train_len, const void *gen_buf,
+                          size_t gen_len);
+
 /* Plain 16-byte grid-stride copy of `bytes` (multiple of 16) from src to dst (DEVICE
  * pointers, 16-byte aligned, not overlapping) on hip_stream: a kernel of known traffic,
  * for calibrating hardware counters and for measuring the copy ceiling of a box.
  * dst == NULL: only reads src; src == NULL: only writes dst (a constant pattern).  Not
  * part of the paper's method. */
 HF_API int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+/* One read, n_dst writes: `bytes` of src go to dst, dst + dst_stride, ..., n_dst places
+ * (1 <= n_dst <= 8; DEVICE pointers, 256-byte aligned; bytes a multiple of 8192;
+ * dst_stride >= bytes, multiple of 256; nothing overlaps).  The traffic mix of a
+ * transition in which every training piece is wanted by n_dst ranks, without any of its
+ * geometry: the ceiling such a mix can reach on a box.
+ * block_bytes == 0: every workgroup loads its part once and stores it n_dst times;
+ * block_bytes > 0 (multiple of 64 KiB): a block of the source is copied to the first place,
+ * then the same block to the second, ... (re-reads served by L2), like the library's
+ * cache-blocked work list.  wg_bytes: bytes per workgroup, 1024 (one wavefront), 4096 or
+ * 8192.  src == NULL: only the n_dst writes (of a constant pattern); dst == NULL: only the
+ * read (block_bytes must then be 0).  Not part of the paper's method. */
+HF_API int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes,
+                    int wg_bytes, void *hip_stream);
 
 /* ---- tuning (host; takes effect on the next launch) -----------------------------
- * HF_PARAM_TILE_BYTES re-tiles and re-uploads (allocates; not for the hot path). */
+ * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES re-tile and re-upload; HF_PARAM_MULTICAST
+ * uploads the work list of the new mode and frees the old one (they allocate; not for the
+ * hot path).  Only the work lists of the current mode are resident on the device. */
 enum {
   HF_PARAM_TILE_BYTES = 0,   /* bytes of work per tile, 4096 .. 4 MiB, multiple of 4096   */
   HF_PARAM_GRID_WGS = 1,     /* workgroups of the persistent kernels, 1 .. 65536          */
@@ -249,11 +307,9 @@ enum {
   HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for plain streaming lists                */
-  HF_PARAM_KIND_MASK = 7     /* profiling aid: bit k set = descriptors of kind k (HF_COL ..
-                                HF_GATEUP_DEINT) are executed and counted by
-                                hf_plan_bytes_moved / hf_plan_unique_src_bytes; default 31
-                                = all.  Any other value makes execute/back INCOMPLETE and
-                                hf_plan_validate fail (re-tiles and re-uploads)          */
+  HF_PARAM_OFFLOAD_WGS = 10  /* persistent workgroups of hf_offload_remote / hf_reload_remote,
+                                1 .. 4096 (default 256: enough to fill the host link, few
+                                enough to leave the GPU to a reshard on another stream)  */
 };
 enum {
   HF_MULTICAST_OFF = 0,       /* one read per destination, destination-major order        */
@@ -277,6 +333,14 @@ enum {
 HF_API int hf_plan_set_param(hf_plan *plan, int param, int64_t value);
 HF_API int64_t hf_plan_get_param(const hf_plan *plan, int param);
 
+/* ---- profiling aid, NOT for production ---------------------------------------------
+ * Restricts the plan to the descriptors of some kinds: bit k of kind_mask set = kind k
+ * (HF_COL .. HF_GATEUP_DEINT) takes part; 31 = all (the state of a new plan).  Serves to
+ * time one tensor kind at a time.  While the mask is not 31, execute / back / install_own
+ * copy ONLY those kinds, hf_plan_bytes_moved / hf_plan_unique_src_bytes count only them
+ * and hf_plan_validate fails.  Re-tiles and re-uploads (allocates). */
+HF_API int hf_debug_restrict_kinds(hf_plan *plan, int kind_mask);
+
 /* ---- queries (host only, no device work) --------------------------------------- */
 HF_API size_t hf_plan_train_bytes(const hf_plan *plan);              /* required size of train_buf */
 HF_API size_t hf_plan_gen_bytes(const hf_plan *plan);                /* required size of gen_buf   */
@@ -290,7 +354,8 @@ HF_API int hf_plan_rank_coords(const hf_plan *plan, int rank, int32_t out[6]);
 HF_API int hf_plan_micro_dp_size(const hf_plan *plan);               /* d_g (Section 5.1)          */
 HF_API size_t hf_plan_num_tensors(const hf_plan *plan, int which_buf, int rank);
 HF_API int hf_plan_get_tensor(const hf_plan *plan, int which_buf, int rank, size_t i, hf_tensor_info *out);
-/* copy descriptors that execute (direction 0) / back (direction 1) perform */
+/* copy descriptors that execute (direction 0) / back (direction 1) / offload (2: src_off
+ * in gen_buf, dst_off in the host image) / reload (3: the other way round) perform */
 HF_API size_t hf_plan_num_desc(const hf_plan *plan, int direction);
 HF_API int hf_plan_get_desc(const hf_plan *plan, int direction, size_t i, hf_desc *out);
 HF_API size_t hf_plan_bytes_moved(const hf_plan *plan, int direction); /* sum n_blocks*rows*row_bytes */
@@ -301,7 +366,7 @@ HF_API size_t hf_plan_unique_src_bytes(const hf_plan *plan, int direction);
  * buffer (src_off in train_buf, dst_off in gen_buf); the zero-redundancy overlap */
 HF_API size_t hf_plan_num_own_view(const hf_plan *plan, int rank);
 HF_API int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out);
-/* device work list of a direction, in launch order (for host-side checking) */
+/* device work list of a direction (0..3), in launch order (for host-side checking) */
 HF_API size_t hf_plan_num_tiles(const hf_plan *plan, int direction);
 HF_API int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out);
 /* k-th destination offset (0 <= k < n_dst) of tile i */

@@ -26,15 +26,17 @@ _lib = C.CDLL(LIB_PATH)
 
 # ---- constants (mirror the header) ----------------------------------------------------
 HF_OK, HF_EINVAL, HF_EDIVIS, HF_ERANGE, HF_ENOMEM, HF_EHIP = 0, -1, -2, -3, -4, -5
-HF_SKIP_OWN, HF_COPY_OWN, HF_GROUPING_VANILLA, HF_PLAN_HOST_ONLY = 0x0, 0x1, 0x2, 0x4
+HF_SKIP_OWN, HF_COPY_OWN, HF_GROUPING_VANILLA, HF_PLAN_HOST_ONLY, HF_PLAN_OFFLOAD = 0x0, 0x1, 0x2, 0x4, 0x8
 (HF_T_EMBED, HF_T_LN1, HF_T_QKV, HF_T_O, HF_T_LN2, HF_T_GATE_UP, HF_T_DOWN, HF_T_LNF, HF_T_HEAD) = range(9)
 (HF_G_EMBED, HF_G_LN1, HF_G_Q, HF_G_K, HF_G_V, HF_G_O, HF_G_LN2, HF_G_GATE, HF_G_UP, HF_G_DOWN, HF_G_LNF,
  HF_G_HEAD) = range(16, 28)
 HF_COL, HF_ROW, HF_REPL, HF_QKV_DEINT, HF_GATEUP_DEINT = range(5)
 HF_DESC_OWN, HF_DESC_ALIGN16, HF_DESC_ALIGN8, HF_DESC_ALIGN4, HF_DESC_ALIGN2 = 0x1, 0x10, 0x20, 0x40, 0x80
-HF_DIR_TRAIN_TO_GEN, HF_DIR_GEN_TO_TRAIN = 0, 1
+HF_DIR_TRAIN_TO_GEN, HF_DIR_GEN_TO_TRAIN, HF_DIR_OFFLOAD, HF_DIR_RELOAD = 0, 1, 2, 3
 HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
-HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_KIND_MASK, HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+(HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES,
+ HF_PARAM_MC_BLOCK_BYTES) = range(7)
+HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS, HF_PARAM_OFFLOAD_WGS = 8, 9, 10
 HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED = 0, 1, 2
 HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED, HF_VARIANT_WAVE_PERSISTENT, HF_VARIANT_PARTS = 0, 1, 2, 3, 4
 
@@ -115,6 +117,13 @@ SIGNATURES = {
     "hf_gather_responses": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hf_plan_micro_dp_peer": (C.c_int, [_P, C.c_int, C.c_int]),
     "hf_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hf_calib_fanout": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p]),
+    "hf_offload_remote": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hf_reload_remote": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hf_plan_remote_bytes": (C.c_size_t, [_P]),
+    "hf_plan_remote_rank_offset": (C.c_size_t, [_P, C.c_int]),
+    "hf_plan_check_buffers": (C.c_int, [_P, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]),
+    "hf_debug_restrict_kinds": (C.c_int, [_P, C.c_int]),
     "hf_plan_validate": (C.c_int, [_P]),
     "hf_last_error": (C.c_char_p, []),
     "hf_version": (C.c_char_p, []),

@@ -27,26 +27,52 @@ int fail(int code, const std::string &msg) {
   return code;
 }
 
-void free_device(hf::Plan &p) {
-  if (p.d_tiles_fwd) (void)hipFree(p.d_tiles_fwd);
-  if (p.d_tiles_back) (void)hipFree(p.d_tiles_back);
-  if (p.d_tiles_fwd_mc) (void)hipFree(p.d_tiles_fwd_mc);
-  if (p.d_mc_dst) (void)hipFree(p.d_mc_dst);
-  if (p.d_tiles_fwd_cb) (void)hipFree(p.d_tiles_fwd_cb);
-  if (p.d_micro_peers) (void)hipFree(p.d_micro_peers);
-  p.d_micro_peers = nullptr;
-  p.d_tiles_fwd = p.d_tiles_back = p.d_tiles_fwd_mc = p.d_tiles_fwd_cb = nullptr;
-  p.d_mc_dst = nullptr;
+template <typename T> void release(T *&ptr) {
+  if (ptr) (void)hipFree(ptr);
+  ptr = nullptr;
 }
 
-template <typename T> int upload_list(const std::vector<T> &v, T **out) {
-  *out = nullptr;
-  if (v.empty()) return HF_OK;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(out), v.size() * sizeof(T));
+void free_device(hf::Plan &p) {
+  release(p.d_tiles_fwd);
+  release(p.d_tiles_own);
+  release(p.d_tiles_back);
+  release(p.d_tiles_fwd_mc);
+  release(p.d_mc_dst);
+  release(p.d_tiles_fwd_cb);
+  release(p.d_tiles_offload);
+  release(p.d_tiles_reload);
+  release(p.d_micro_peers);
+}
+
+template <typename T> int upload_list(const T *v, size_t n, T **out) {
+  release(*out);
+  if (n == 0) return HF_OK;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(out), n * sizeof(T));
   if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? HF_ENOMEM : HF_EHIP, std::string("hipMalloc: ") + hipGetErrorString(e));
-  e = hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+  e = hipMemcpy(*out, v, n * sizeof(T), hipMemcpyHostToDevice);
   if (e != hipSuccess) return fail(HF_EHIP, std::string("hipMemcpy: ") + hipGetErrorString(e));
   return HF_OK;
+}
+template <typename T> int upload_list(const std::vector<T> &v, T **out) { return upload_list(v.data(), v.size(), out); }
+
+// Makes resident exactly the train->gen work list that the current multicast mode runs
+// (and frees the others).  Called at plan time and from hf_plan_set_param, never from an
+// execution entry point.
+int upload_forward_lists(hf::Plan &p) {
+  const int64_t mode = p.effective_multicast();
+  int rc = HF_OK;
+  if (mode == HF_MULTICAST_OFF) rc = upload_list(p.tiles_fwd.data(), (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer, &p.d_tiles_fwd);
+  else release(p.d_tiles_fwd);
+  if (rc == HF_OK && mode == HF_MULTICAST_REGISTERS) {
+    rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
+    if (rc == HF_OK) rc = upload_list(p.mc_dst, &p.d_mc_dst);
+  } else {
+    release(p.d_tiles_fwd_mc);
+    release(p.d_mc_dst);
+  }
+  if (rc == HF_OK && mode == HF_MULTICAST_CACHE_BLOCKED) rc = upload_list(p.tiles_fwd_cb, &p.d_tiles_fwd_cb);
+  else release(p.d_tiles_fwd_cb);
+  return rc;
 }
 
 int upload(hf::Plan &p) {
@@ -55,11 +81,11 @@ int upload(hf::Plan &p) {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return fail(HF_EHIP, std::string("no HIP device: ") + hipGetErrorString(e));
   p.device = dev;
-  int rc = upload_list(p.tiles_fwd, &p.d_tiles_fwd);
+  int rc = upload_forward_lists(p);
+  if (rc == HF_OK) rc = upload_list(p.tiles_fwd.data() + p.n_tiles_fwd_peer, p.tiles_fwd.size() - p.n_tiles_fwd_peer, &p.d_tiles_own);
   if (rc == HF_OK) rc = upload_list(p.tiles_back, &p.d_tiles_back);
-  if (rc == HF_OK) rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
-  if (rc == HF_OK) rc = upload_list(p.mc_dst, &p.d_mc_dst);
-  if (rc == HF_OK) rc = upload_list(p.tiles_fwd_cb, &p.d_tiles_fwd_cb);
+  if (rc == HF_OK) rc = upload_list(p.tiles_offload, &p.d_tiles_offload);
+  if (rc == HF_OK) rc = upload_list(p.tiles_reload, &p.d_tiles_reload);
   if (rc == HF_OK) rc = upload_list(p.micro_peers, &p.d_micro_peers);
   if (rc != HF_OK) free_device(p);
   return rc;
@@ -167,11 +193,98 @@ int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf
   return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream);
 }
 
+// host_buf must be pinned host memory; returns the address the device uses for it
+static int device_view_of_pinned(const void *host_buf, size_t bytes, void **out) {
+  hipPointerAttribute_t at;
+  std::memset(&at, 0, sizeof at);
+  if (hipPointerGetAttributes(&at, host_buf) != hipSuccess) {
+    (void)hipGetLastError(); // an unknown pointer leaves a sticky error behind
+    return fail(HF_EINVAL, "host_buf is not known to the HIP runtime: it must be pinned host memory (hipHostMalloc)");
+  }
+  if (at.type != hipMemoryTypeHost || !at.devicePointer)
+    return fail(HF_EINVAL, "host_buf must be pinned host memory that the device can address (hipHostMalloc)");
+  void *base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(reinterpret_cast<hipDeviceptr_t *>(&base), &size, at.devicePointer) == hipSuccess && base) {
+    const char *lo = static_cast<const char *>(base), *p0 = static_cast<const char *>(at.devicePointer);
+    if (p0 < lo || p0 + bytes > lo + size) return fail(HF_EINVAL, "host_buf is shorter than hf_plan_remote_bytes");
+  } else {
+    (void)hipGetLastError();
+  }
+  *out = at.devicePointer;
+  return HF_OK;
+}
+
+static int offload_common(const hf_plan *plan, const void *gen_buf, const void *host_buf, void **host_dev) {
+  if (!plan || !gen_buf || !host_buf) return fail(HF_EINVAL, "null plan or buffer");
+  const hf::Plan &p = plan->p;
+  if (p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
+  if (!(p.flags & HF_PLAN_OFFLOAD)) return fail(HF_EINVAL, "plan was built without HF_PLAN_OFFLOAD");
+  if (p.kind_mask != 0x1F) return fail(HF_EINVAL, "plan is restricted to some descriptor kinds");
+  if ((reinterpret_cast<uintptr_t>(gen_buf) | reinterpret_cast<uintptr_t>(host_buf)) % 256)
+    return fail(HF_EINVAL, "gen_buf and host_buf must be 256-byte aligned");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != p.device)
+    return fail(HF_EINVAL, "the current HIP device is not the one the plan was built on");
+  return device_view_of_pinned(host_buf, p.remote_bytes, host_dev);
+}
+
+// The host link, not HBM, bounds these two: a few hundred persistent workgroups keep it
+// full and leave most of the GPU to whatever runs on other streams.
+static int launch_link(const hf::Plan &p, const hf_tile *tiles, size_t n, const void *src, void *dst, void *stream) {
+  const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : 0;
+  const int e = hf::launch_tiles(tiles, n, nullptr, src, dst, HF_VARIANT_PERSISTENT, (int)p.offload_wgs, policy,
+                                 (uint32_t)p.tile_bytes, 4096u, (uint32_t)p.max_wgs_per_launch, 256, stream);
+  if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
+  return HF_OK;
+}
+
+int hf_offload_remote(const hf_plan *plan, const void *gen_buf, void *host_buf, void *hip_stream) {
+  void *hd = nullptr;
+  if (int rc = offload_common(plan, gen_buf, host_buf, &hd)) return rc;
+  return launch_link(plan->p, plan->p.d_tiles_offload, plan->p.tiles_offload.size(), gen_buf, hd, hip_stream);
+}
+
+int hf_reload_remote(const hf_plan *plan, const void *host_buf, void *gen_buf, void *hip_stream) {
+  void *hd = nullptr;
+  if (int rc = offload_common(plan, gen_buf, host_buf, &hd)) return rc;
+  return launch_link(plan->p, plan->p.d_tiles_reload, plan->p.tiles_reload.size(), hd, gen_buf, hip_stream);
+}
+
+size_t hf_plan_remote_bytes(const hf_plan *plan) { return plan ? plan->p.remote_bytes : 0; }
+size_t hf_plan_remote_rank_offset(const hf_plan *plan, int rank) {
+  if (!plan || rank < 0 || rank >= plan->p.N || plan->p.mat_pos[rank] < 0) return (size_t)-1;
+  return plan->p.remote_rank_off[plan->p.mat_pos[rank]];
+}
+
+int hf_plan_check_buffers(const hf_plan *plan, const void *train_buf, size_t train_len, const void *gen_buf, size_t gen_len) {
+  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
+  const hf::Plan &p = plan->p;
+  if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
+    return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
+  if (train_len < p.train_bytes) return fail(HF_EINVAL, "train_buf is shorter than hf_plan_train_bytes");
+  if (gen_len < p.gen_bytes) return fail(HF_EINVAL, "gen_buf is shorter than hf_plan_gen_bytes");
+  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
+  if (t0 < g0 + p.gen_bytes && g0 < t0 + p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
+  if (p.flags & HF_PLAN_HOST_ONLY) return HF_OK;
+  struct { const char *ptr; size_t need; const char *name; } bufs[] = {{t0, p.train_bytes, "train_buf"}, {g0, p.gen_bytes, "gen_buf"}};
+  for (auto &b : bufs) {
+    void *base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(reinterpret_cast<hipDeviceptr_t *>(&base), &size, const_cast<char *>(b.ptr)) != hipSuccess || !base) {
+      (void)hipGetLastError();
+      return fail(HF_ERANGE, std::string(b.name) + " is not inside a device allocation of the HIP runtime");
+    }
+    if (b.ptr + b.need > static_cast<const char *>(base) + size)
+      return fail(HF_ERANGE, std::string(b.name) + ": the device allocation ends before the bytes the plan needs");
+  }
+  return HF_OK;
+}
+
 int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
-  return launch(p, p.d_tiles_fwd + p.n_tiles_fwd_peer, p.tiles_fwd.size() - p.n_tiles_fwd_peer, nullptr, train_buf, gen_buf,
-                hip_stream);
+  return launch(p, p.d_tiles_own, p.tiles_fwd.size() - p.n_tiles_fwd_peer, nullptr, train_buf, gen_buf, hip_stream);
 }
 
 int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream) {
@@ -220,6 +333,11 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
   case HF_PARAM_MULTICAST:
     if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_CACHE_BLOCKED) return fail(HF_EINVAL, "unknown multicast mode");
     p.multicast = value;
+    if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
+    return HF_OK;
+  case HF_PARAM_OFFLOAD_WGS:
+    if (value < 1 || value > 4096) return fail(HF_EINVAL, "offload workgroups must be in [1, 4096]");
+    p.offload_wgs = value;
     return HF_OK;
   case HF_PARAM_MC_BLOCK_BYTES: {
     if (value < (1 << 20) || value > (1ll << 30)) return fail(HF_EINVAL, "multicast block must be in [1 MiB, 1 GiB]");
@@ -234,10 +352,6 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     if (value != 0 && value != 64 && value != 256) return fail(HF_EINVAL, "workgroup size must be 0 (automatic), 64 or 256");
     p.wg_threads = value;
     return HF_OK;
-  case HF_PARAM_KIND_MASK:
-    if (value < 1 || value > 0x1F) return fail(HF_EINVAL, "kind mask must be in [1, 31]");
-    p.kind_mask = value;
-    return retile(p, p.tile_bytes);
   case HF_PARAM_CACHE_POLICY:
     if (value < -1 || value > 5) return fail(HF_EINVAL, "cache policy must be in [-1, 5]");
     p.cache_policy = value;
@@ -251,6 +365,13 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
   return fail(HF_EINVAL, "unknown parameter");
 }
 
+int hf_debug_restrict_kinds(hf_plan *plan, int kind_mask) {
+  if (!plan) return fail(HF_EINVAL, "null plan");
+  if (kind_mask < 1 || kind_mask > 0x1F) return fail(HF_EINVAL, "kind mask must be in [1, 31]");
+  plan->p.kind_mask = kind_mask;
+  return retile(plan->p, plan->p.tile_bytes);
+}
+
 int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   if (!plan) return -1;
   switch (param) {
@@ -259,7 +380,7 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_VARIANT: return plan->p.variant;
   case HF_PARAM_MULTICAST: return plan->p.effective_multicast();
   case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
-  case HF_PARAM_KIND_MASK: return plan->p.kind_mask;
+  case HF_PARAM_OFFLOAD_WGS: return plan->p.offload_wgs;
   case HF_PARAM_WG_THREADS: return plan->p.wg_threads;
   case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;
@@ -330,6 +451,7 @@ static const hf_desc *desc_at(const hf::Plan &p, int direction, size_t i) {
     return nullptr;
   }
   if (direction == HF_DIR_GEN_TO_TRAIN && i < p.back.size()) return &p.back[i];
+  if ((direction == HF_DIR_OFFLOAD || direction == HF_DIR_RELOAD) && i < p.remote.size()) return &p.remote[i];
   return nullptr;
 }
 
@@ -338,6 +460,7 @@ size_t hf_plan_num_desc(const hf_plan *plan, int direction) {
   const hf::Plan &p = plan->p;
   if (direction == HF_DIR_TRAIN_TO_GEN) return p.fwd_peer.size() + ((p.flags & HF_COPY_OWN) ? p.fwd_own.size() : 0);
   if (direction == HF_DIR_GEN_TO_TRAIN) return p.back.size();
+  if (direction == HF_DIR_OFFLOAD || direction == HF_DIR_RELOAD) return p.remote.size();
   return 0;
 }
 
@@ -346,27 +469,30 @@ int hf_plan_get_desc(const hf_plan *plan, int direction, size_t i, hf_desc *out)
   const hf_desc *d = desc_at(plan->p, direction, i);
   if (!d) return fail(HF_ERANGE, "no such descriptor");
   *out = *d;
+  if (direction == HF_DIR_RELOAD) {
+    std::swap(out->src_off, out->dst_off);
+    std::swap(out->src_block_stride, out->dst_block_stride);
+    std::swap(out->src_row_stride, out->dst_row_stride);
+  }
   return HF_OK;
 }
 
+// totals are cached when the work lists are built
 size_t hf_plan_bytes_moved(const hf_plan *plan, int direction) {
   if (!plan) return 0;
-  size_t total = 0;
-  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) {
-    const hf_desc *d = desc_at(plan->p, direction, i);
-    if ((plan->p.kind_mask >> d->kind) & 1) total += hf::desc_bytes(*d);
+  if (direction == HF_DIR_TRAIN_TO_GEN || direction == HF_DIR_GEN_TO_TRAIN) return plan->p.moved_bytes[direction];
+  if (direction == HF_DIR_OFFLOAD || direction == HF_DIR_RELOAD) {
+    size_t total = 0;
+    for (const hf_desc &d : plan->p.remote) total += hf::desc_bytes(d);
+    return total;
   }
-  return total;
+  return 0;
 }
 
 size_t hf_plan_unique_src_bytes(const hf_plan *plan, int direction) {
   if (!plan) return 0;
-  std::vector<const hf_desc *> v;
-  for (size_t i = 0, n = hf_plan_num_desc(plan, direction); i < n; ++i) {
-    const hf_desc *d = desc_at(plan->p, direction, i);
-    if ((plan->p.kind_mask >> d->kind) & 1) v.push_back(d);
-  }
-  return hf::unique_src_bytes(v);
+  if (direction == HF_DIR_TRAIN_TO_GEN || direction == HF_DIR_GEN_TO_TRAIN) return plan->p.unique_bytes[direction];
+  return hf_plan_bytes_moved(plan, direction); // the image holds every remote piece once
 }
 
 size_t hf_plan_num_own_view(const hf_plan *plan, int rank) {
@@ -394,6 +520,8 @@ size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
   if (direction == HF_DIR_TRAIN_TO_GEN && p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED) return p.tiles_fwd_cb.size();
   if (direction == HF_DIR_TRAIN_TO_GEN) return (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   if (direction == HF_DIR_GEN_TO_TRAIN) return p.tiles_back.size();
+  if (direction == HF_DIR_OFFLOAD) return p.tiles_offload.size();
+  if (direction == HF_DIR_RELOAD) return p.tiles_reload.size();
   return 0;
 }
 
@@ -402,6 +530,8 @@ int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out)
   if (i >= hf_plan_num_tiles(plan, direction)) return fail(HF_ERANGE, "no such tile");
   const hf::Plan &p = plan->p;
   *out = direction == HF_DIR_GEN_TO_TRAIN                    ? p.tiles_back[i]
+         : direction == HF_DIR_OFFLOAD                           ? p.tiles_offload[i]
+         : direction == HF_DIR_RELOAD                            ? p.tiles_reload[i]
          : p.effective_multicast() == HF_MULTICAST_REGISTERS     ? p.tiles_fwd_mc[i]
          : p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb[i]
                                                               : p.tiles_fwd[i];
@@ -424,6 +554,24 @@ int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
   const char *s = static_cast<const char *>(src), *d = static_cast<const char *>(dst);
   if (s && d && s < d + bytes && d < s + bytes) return fail(HF_EINVAL, "calibration copy: buffers overlap");
   const int e = hf::launch_calib_copy(src, dst, bytes, hip_stream);
+  if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
+  return HF_OK;
+}
+
+int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes, int wg_bytes,
+                    void *hip_stream) {
+  if (!src && !dst) return fail(HF_EINVAL, "null buffers");
+  if ((!src || !dst) && block_bytes) return fail(HF_EINVAL, "fan-out copy: blocks need both a source and destinations");
+  if (n_dst < 1 || n_dst > 8) return fail(HF_EINVAL, "n_dst must be in [1, 8]");
+  if (wg_bytes != 1024 && wg_bytes != 4096 && wg_bytes != 8192) return fail(HF_EINVAL, "wg_bytes must be 1024, 4096 or 8192");
+  if (bytes == 0 || bytes % 8192 || dst_stride % 256 || dst_stride < bytes || block_bytes % 65536 ||
+      (reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) % 256)
+    return fail(HF_EINVAL, "fan-out copy: sizes or alignment out of contract");
+  const char *s0 = static_cast<const char *>(src), *d0 = static_cast<const char *>(dst);
+  const size_t span = (size_t)(n_dst - 1) * dst_stride + bytes;
+  if (s0 && d0 && s0 < d0 + span && d0 < s0 + bytes) return fail(HF_EINVAL, "fan-out copy: buffers overlap");
+  const int e = hf::launch_calib_fanout(src, dst, bytes, n_dst, dst_stride, block_bytes, wg_bytes, hip_stream);
+  if (e == (int)hipErrorInvalidValue) return fail(HF_ERANGE, "fan-out copy: too many workgroups for one launch");
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }

@@ -50,6 +50,12 @@ struct Plan {
   std::vector<hf_desc> fwd_peer, fwd_own;
   // step 4 (gen -> train): inverse of the own pieces
   std::vector<hf_desc> back;
+  // offload image (host side of hf_offload_remote / hf_reload_remote): one descriptor per
+  // peer descriptor, src_off = where the piece sits in gen_buf, dst_off = where it sits in
+  // the packed host image; remote_rank_off[i] = start of the i-th materialised rank's part
+  std::vector<hf_desc> remote;
+  std::vector<uint64_t> remote_rank_off;
+  uint64_t remote_bytes = 0;
 
   // device work lists; tiles_fwd = [peer tiles | own tiles], one destination per tile
   std::vector<hf_tile> tiles_fwd, tiles_back;
@@ -60,6 +66,8 @@ struct Plan {
   std::vector<uint64_t> mc_dst;
   // the same work, one destination per tile, in cache-blocked order (see build_tiles)
   std::vector<hf_tile> tiles_fwd_cb;
+  // offload / reload work lists (only with HF_PLAN_OFFLOAD): gen_buf -> image and back
+  std::vector<hf_tile> tiles_offload, tiles_reload;
   bool has_sharing = false; // some training piece has more than one destination
   // multicast mode that execute really uses: without sharing the multicast lists are the
   // one-destination work in another order, and the plain list with streaming loads is faster
@@ -74,14 +82,24 @@ struct Plan {
   int64_t part_bytes = 0; // 0 = chosen per launch
   int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
   int64_t wg_threads = 0; // 0 = chosen per launch
-  int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (profiling aid)
+  int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (hf_debug_restrict_kinds)
+  int64_t offload_wgs = 256; // persistent workgroups of the offload / reload kernels
+  // totals of the descriptors that take part, per direction (set by build_tiles)
+  uint64_t moved_bytes[2] = {0, 0}, unique_bytes[2] = {0, 0};
 
   // device copy (null for HF_PLAN_HOST_ONLY)
   int device = -1;
+  // Only the lists the current multicast mode needs are resident: d_tiles_fwd (the whole
+  // one-destination list) for HF_MULTICAST_OFF, d_tiles_fwd_mc + d_mc_dst for
+  // HF_MULTICAST_REGISTERS, d_tiles_fwd_cb for HF_MULTICAST_CACHE_BLOCKED; the own tiles
+  // (hf_reshard_install_own), the reverse list and the group table always.
   hf_tile *d_tiles_fwd = nullptr;
+  hf_tile *d_tiles_own = nullptr;
   hf_tile *d_tiles_back = nullptr;
   hf_tile *d_tiles_fwd_mc = nullptr;
   hf_tile *d_tiles_fwd_cb = nullptr;
+  hf_tile *d_tiles_offload = nullptr;
+  hf_tile *d_tiles_reload = nullptr;
   uint64_t *d_mc_dst = nullptr;
   int32_t *d_micro_peers = nullptr;
 };

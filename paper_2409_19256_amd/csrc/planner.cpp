@@ -153,7 +153,7 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
     if (v <= 0) { err = "all model and layout sizes must be positive"; return HF_EINVAL; }
   if (m.elem_bytes != 2) { err = "elem_bytes must be 2 (bf16)"; return HF_EINVAL; }
   if (m.tied_embed != 0) { err = "tied embedding / LM head is not supported"; return HF_EINVAL; }
-  if (gl.flags & ~(HF_COPY_OWN | HF_GROUPING_VANILLA | HF_PLAN_HOST_ONLY)) { err = "unknown flag bits"; return HF_EINVAL; }
+  if (gl.flags & ~(HF_COPY_OWN | HF_GROUPING_VANILLA | HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD)) { err = "unknown flag bits"; return HF_EINVAL; }
   if (gl.mat_ranks && gl.n_mat <= 0) { err = "mat_ranks given but n_mat <= 0"; return HF_EINVAL; }
   struct { bool bad; const char *what; } div[] = {
       {tl.tp % gl.tp != 0, "t % t_g"}, {tl.pp % gl.pp != 0, "p % p_g"}, {m.n_layers % tl.pp != 0, "L % p"},
@@ -314,6 +314,67 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
       pl.back.push_back(d);
     }
   }
+
+  // ---- offload image of the remote pieces (Section 7: the generation copy of the weights
+  // leaves the GPU while the model trains).  The peer descriptors of one (rank, generation
+  // tensor) are consecutive and ordered by the position of their piece in the tensor, so
+  // the remote elements of the tensor in row-major order are: for column-parallel kinds the
+  // pieces one after another, for row-parallel kinds a matrix [rows, n_remote * piece cols].
+  // Tensor parts start at 256-byte boundaries, rank parts at 4096-byte boundaries.
+  {
+    uint64_t hoff = 0;
+    int cur_rank = -1;
+    for (size_t i = 0; i < pl.fwd_peer.size();) {
+      const hf_desc &d0 = pl.fwd_peer[i];
+      size_t j = i + 1;
+      while (j < pl.fwd_peer.size() && pl.fwd_peer[j].dst_rank == d0.dst_rank && pl.fwd_peer[j].tensor_id == d0.tensor_id &&
+             pl.fwd_peer[j].layer == d0.layer)
+        ++j;
+      if (d0.dst_rank != cur_rank) {
+        // ranks appear in buffer order; a rank without remote pieces gets an empty part
+        while (pl.remote_rank_off.size() <= (size_t)pl.mat_pos[d0.dst_rank]) {
+          hoff = round_up(hoff, kRankAlign);
+          pl.remote_rank_off.push_back(hoff);
+        }
+        cur_rank = d0.dst_rank;
+      }
+      hoff = round_up(hoff, kTensorAlign);
+      const uint64_t n_remote = j - i;
+      for (size_t k = i; k < j; ++k) {
+        const hf_desc &f = pl.fwd_peer[k];
+        hf_desc d;
+        std::memset(&d, 0, sizeof d);
+        d.src_rank = d.dst_rank = f.dst_rank;
+        d.tensor_id = f.tensor_id;
+        d.layer = f.layer;
+        d.kind = f.kind;
+        d.src_off = f.dst_off;
+        d.n_blocks = 1;
+        d.row_bytes = f.row_bytes;
+        if (f.kind == HF_ROW) {
+          d.rows = f.rows;
+          d.src_row_stride = f.dst_row_stride;
+          d.dst_row_stride = n_remote * f.row_bytes;
+          d.dst_off = hoff + (k - i) * f.row_bytes;
+        } else { // contiguous in the generation tensor
+          d.rows = f.n_blocks * f.rows;
+          d.src_row_stride = d.dst_row_stride = f.row_bytes;
+          d.dst_off = hoff + (k - i) * desc_bytes(f);
+        }
+        d.src_block_stride = (uint64_t)d.rows * d.src_row_stride;
+        d.dst_block_stride = (uint64_t)d.rows * d.dst_row_stride;
+        d.flags = desc_align(d);
+        pl.remote.push_back(d);
+      }
+      hoff += n_remote * desc_bytes(d0);
+      i = j;
+    }
+    while (pl.remote_rank_off.size() < pl.mat.size()) {
+      hoff = round_up(hoff, kRankAlign);
+      pl.remote_rank_off.push_back(hoff);
+    }
+    pl.remote_bytes = round_up(hoff, kRankAlign);
+  }
   return build_tiles(pl, err);
 }
 
@@ -415,6 +476,29 @@ int build_tiles(Plan &pl, std::string &err) {
   pl.n_tiles_fwd_peer = pl.tiles_fwd.size();
   tile_list(pl.fwd_own, pl.tiles_fwd);
   tile_list(pl.back, pl.tiles_back);
+  pl.tiles_offload.clear();
+  pl.tiles_reload.clear();
+  if (pl.flags & HF_PLAN_OFFLOAD) {
+    for (const hf_desc &d : pl.remote) tile_desc(pl.tiles_offload, d, (uint64_t)pl.tile_bytes);
+    pl.tiles_reload = pl.tiles_offload;
+    for (hf_tile &t : pl.tiles_reload) {
+      std::swap(t.src_off, t.dst_off);
+      std::swap(t.src_row_stride, t.dst_row_stride);
+    }
+  }
+  // totals of the descriptors that take part (queried on the hot path of harnesses)
+  {
+    std::vector<const hf_desc *> fwd, back;
+    for (const hf_desc &d : pl.fwd_peer) if (wanted(d)) fwd.push_back(&d);
+    if (pl.flags & HF_COPY_OWN)
+      for (const hf_desc &d : pl.fwd_own) if (wanted(d)) fwd.push_back(&d);
+    for (const hf_desc &d : pl.back) if (wanted(d)) back.push_back(&d);
+    pl.moved_bytes[0] = pl.moved_bytes[1] = 0;
+    for (const hf_desc *d : fwd) pl.moved_bytes[0] += desc_bytes(*d);
+    for (const hf_desc *d : back) pl.moved_bytes[1] += desc_bytes(*d);
+    pl.unique_bytes[0] = unique_src_bytes(fwd);
+    pl.unique_bytes[1] = unique_src_bytes(back);
+  }
 
   // multicast list over the descriptors execute performs: same source bytes and same
   // geometry -> one tile with several destinations, in order of first appearance
@@ -586,7 +670,7 @@ int train_id_of(int gen_id) {
 } // namespace
 
 int validate_plan(const Plan &pl, std::string &err) {
-  if (pl.kind_mask != 0x1F) { err = "plan is restricted to some descriptor kinds (HF_PARAM_KIND_MASK)"; return HF_EINVAL; }
+  if (pl.kind_mask != 0x1F) { err = "plan is restricted to some descriptor kinds (hf_debug_restrict_kinds)"; return HF_EINVAL; }
   // (1) every descriptor stays inside the payload of the tensors it names
   auto inside = [&](const hf_desc &d, bool forward) -> bool {
     const int train_rank = forward ? d.src_rank : d.dst_rank, gen_rank = forward ? d.dst_rank : d.src_rank;
@@ -656,7 +740,41 @@ int validate_plan(const Plan &pl, std::string &err) {
   }
   if (!normalise(cb, err, "cache-blocked tiles")) return HF_ERANGE;
   if (!same(cb, mc)) { err = "cache-blocked tiles differ from descriptors"; return HF_ERANGE; }
-  for (const std::vector<hf_tile> *lst : {&pl.tiles_fwd, &pl.tiles_back})
+  // (4) offload image: its generation side is exactly the peer destinations, its host side
+  // is pairwise disjoint and inside the image; the offload tiles are its descriptors
+  {
+    std::vector<Seg> gen_side, host_side, peers = fwd_peer_only, tiles;
+    for (const hf_desc &d : pl.remote) {
+      std::vector<Seg> one;
+      desc_segments(d, one); // Seg.dst = host image offset, Seg.src = generation offset
+      for (const Seg &s : one) {
+        if (s.dst + s.len > pl.remote_bytes) { err = "offload descriptor leaves the image"; return HF_ERANGE; }
+        host_side.push_back(s);
+        gen_side.push_back({s.src, s.src, s.len});
+      }
+    }
+    for (Seg &s : peers) s.src = s.dst; // compare coverage of gen_buf only
+    std::vector<Seg> host_sorted = host_side;
+    if (!normalise(host_sorted, err, "offload image") || !normalise(gen_side, err, "offload sources") ||
+        !normalise(peers, err, "peer destinations"))
+      return HF_ERANGE;
+    if (!same(gen_side, peers)) { err = "offload image does not cover the remote pieces"; return HF_ERANGE; }
+    if (pl.flags & HF_PLAN_OFFLOAD) {
+      for (const hf_tile &t : pl.tiles_offload) tile_segments(t, tiles);
+      if (!normalise(tiles, err, "offload tiles")) return HF_ERANGE;
+      if (!same(tiles, host_sorted)) { err = "offload tiles differ from descriptors"; return HF_ERANGE; }
+      if (pl.tiles_reload.size() != pl.tiles_offload.size()) { err = "reload tiles differ from offload tiles"; return HF_ERANGE; }
+      for (size_t i = 0; i < pl.tiles_reload.size(); ++i) {
+        const hf_tile &x = pl.tiles_offload[i], &y = pl.tiles_reload[i];
+        if (x.src_off != y.dst_off || x.dst_off != y.src_off || x.src_row_stride != y.dst_row_stride ||
+            x.dst_row_stride != y.src_row_stride || x.rows != y.rows || x.row_bytes != y.row_bytes || x.vec_bytes != y.vec_bytes) {
+          err = "reload tiles differ from offload tiles";
+          return HF_ERANGE;
+        }
+      }
+    }
+  }
+  for (const std::vector<hf_tile> *lst : {&pl.tiles_fwd, &pl.tiles_back, &pl.tiles_offload, &pl.tiles_reload})
     for (const hf_tile &t : *lst) {
       uint64_t g = t.src_off | t.dst_off | t.row_bytes;
       if (t.rows > 1) g |= (uint64_t)t.src_row_stride | t.dst_row_stride;

@@ -1,15 +1,26 @@
 // gfx950 copy kernels that execute a reshard plan's tile list.
 //
 // The work is pure data movement (HybridFlow Section 5.2 steps 1 and 4 re-arrange
-// parameters, they compute nothing), so the kernels are shaped for HBM bandwidth:
-// every lane moves 16 bytes per access (8/4/2 when a tile is less aligned), a wavefront
-// therefore touches 1 KiB of consecutive bytes per instruction, eight independent loads
-// are issued per lane before the first store so that each CU keeps tens of KiB in
-// flight, and the grid is a fixed number of persistent workgroups that stride over the
-// tile list (tile i -> workgroup i mod grid), which keeps the workgroups that run at the
-// same time on neighbouring tiles of the same tensors.  A tile may name several
-// destinations (one training piece wanted by several ranks of a micro-DP group,
-// Section 5.3): it is loaded once and stored to each.  No MFMA: there is no arithmetic.
+// parameters, they compute nothing), so the kernels are shaped for HBM bandwidth and use
+// no MFMA and, in the default path, no LDS.  Every lane moves 16 bytes per access (8/4/2
+// when a tile is less aligned), so a wavefront touches 1 KiB of consecutive bytes per
+// instruction.
+//
+// Default kernel, reshard_parts: the tile list (tiles of about 128 KiB) is cut into parts
+// of 1 to 8 KiB and every part gets its own short-lived workgroup of 64 or 256 lanes,
+// which loads its one or two vectors per lane, stores them and exits.  The hardware
+// dispatcher hands out workgroups in index order, so the chip works on one narrow window
+// of source and destination addresses that moves through the list, and a slow CU simply
+// takes fewer workgroups.  One training piece wanted by several ranks of a micro-DP group
+// (Section 5.3) is served either by listing its tiles once per destination in an order
+// that lets L2 serve the re-reads (cache-blocked list, the default) or by tiles that name
+// several destinations (loaded once, stored to each).
+//
+// Kept beside it, selectable per plan, for measurements: persistent workgroups that stride
+// over the tile list, the same with one wavefront per stride (wavefront-level dispatch),
+// the same staged through LDS, and one workgroup per tile.  The persistent kernel also
+// carries the offload / reload of the remote pieces, where the host link is the bound and
+// few workgroups are wanted.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -44,8 +55,11 @@ template <typename V, int kPolicy> __device__ __forceinline__ void store_stream(
     *reinterpret_cast<V *>(p) = v;
   } else if constexpr (sizeof(V) == 16 && !(kPolicy & 4)) {
     // a vector store like any other to the hardware; the compiler's own wait counts stay
-    // correct because an extra outstanding store can only make its vmcnt waits longer
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+    // correct because an extra outstanding store can only make its vmcnt waits longer.  The
+    // compiler does not see a memory instruction here, so the wait state gfx9 wants between
+    // a store of more than 64 bits and a vector instruction that overwrites its data
+    // registers is supplied by hand.
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 0" : : "v"(p), "v"(v) : "memory");
   } else {
     __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
   }
@@ -230,20 +244,69 @@ __global__ __launch_bounds__(kWG) void gather_slots(const int32_t *__restrict__ 
   if (i < slot_vecs) out[(uint64_t)pair * slot_vecs + i] = in[(uint64_t)peers[pair] * slot_vecs + i];
 }
 
+// a loaded vector is "used" without any store: an empty instruction sequence that takes
+// the four registers as inputs keeps the loads from being optimised away
+__device__ __forceinline__ void keep_alive(const u32x4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+
 // read-only and write-only counterparts of calib_copy (ceilings of one direction)
-__device__ uint32_t calib_sink; // only ever written by calib_read, never read
 __global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec) {
   const size_t stride = (size_t)gridDim.x * kWG;
   u32x4 acc = {0, 0, 0, 0};
   for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
-  // data dependent and rare: keeps the loads alive without a store stream; the caller's
-  // buffers are never written
-  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) calib_sink = acc.x;
+  keep_alive(acc);
 }
 __global__ __launch_bounds__(kWG) void calib_write(u32x4 *__restrict__ dst, size_t n_vec) {
   const size_t stride = (size_t)gridDim.x * kWG;
   const u32x4 v = {0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au};
   for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) __builtin_nontemporal_store(v, dst + i);
+}
+
+// One read, n_dst writes (hf_calib_fanout); src == null: writes only, dst == null: the
+// read only.  Workgroup b of a block pass copies
+// kUnroll vectors per lane; block_vecs == 0: every workgroup stores its vectors to all
+// n_dst places; otherwise the grid is (blocks x n_dst passes x workgroups per block) and
+// a workgroup stores to the place of its pass, so that passes 2.. re-read what pass 1
+// brought into L2.
+template <int kThreads, int kUnroll>
+__global__ __launch_bounds__(kThreads) void calib_fanout(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n_vec,
+                                                         uint32_t n_dst, size_t stride_vec, uint32_t block_vecs) {
+  constexpr uint32_t per_wg = kThreads * kUnroll;
+  size_t first;
+  uint32_t pass = 0;
+  if (block_vecs == 0) {
+    first = (size_t)blockIdx.x * per_wg;
+  } else {
+    const uint32_t wpb = block_vecs / per_wg; // workgroups per block pass
+    const uint32_t block = blockIdx.x / (wpb * n_dst), rest = blockIdx.x - block * (wpb * n_dst);
+    pass = rest / wpb;
+    first = (size_t)block * block_vecs + (size_t)(rest - pass * wpb) * per_wg;
+  }
+  u32x4 v[kUnroll];
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) {
+    const size_t i = first + (size_t)k * kThreads + threadIdx.x;
+    v[k] = u32x4{0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au};
+    if (src && i < n_vec) v[k] = block_vecs ? src[i] : __builtin_nontemporal_load(src + i);
+  }
+  if (!dst) { // read only
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) keep_alive(v[k]);
+    return;
+  }
+  if (block_vecs == 0) {
+    for (uint32_t j = 0; j < n_dst; ++j)
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k) {
+        const size_t i = first + (size_t)k * kThreads + threadIdx.x;
+        if (i < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)j * stride_vec + i);
+      }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+      const size_t i = first + (size_t)k * kThreads + threadIdx.x;
+      if (i < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)pass * stride_vec + i);
+    }
+  }
 }
 
 template <int kPolicy>
@@ -338,6 +401,28 @@ int launch_gather_slots(const int32_t *d_peers, uint32_t n_pairs, const void *in
   else
     hipLaunchKernelGGL(gather_slots<uint32_t>, grid, dim3(kWG), 0, st, d_peers, n_pairs, (uint32_t)chunks, slot_vecs,
                        static_cast<const uint32_t *>(in), static_cast<uint32_t *>(out));
+  return (int)hipGetLastError();
+}
+
+int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes,
+                        int wg_bytes, void *stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t n_vec = bytes / 16, stride_vec = dst_stride / 16;
+  const size_t wgs_one_pass = (bytes + wg_bytes - 1) / wg_bytes;
+  size_t grid = wgs_one_pass;
+  if (block_bytes) {
+    const size_t blocks = (bytes + block_bytes - 1) / block_bytes;
+    grid = blocks * (size_t)n_dst * (block_bytes / wg_bytes);
+  }
+  const int threads = wg_bytes == 1024 ? kWave : kWG;
+  if (grid == 0 || grid > 0xFFFFFFFFull / threads) return (int)hipErrorInvalidValue; // beyond one HIP grid
+  const dim3 g((uint32_t)grid);
+  const u32x4 *s = static_cast<const u32x4 *>(src);
+  u32x4 *d = static_cast<u32x4 *>(dst);
+  const uint32_t bv = (uint32_t)(block_bytes / 16);
+  if (wg_bytes == 1024) hipLaunchKernelGGL((calib_fanout<kWave, 1>), g, dim3(kWave), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
+  else if (wg_bytes == 4096) hipLaunchKernelGGL((calib_fanout<kWG, 1>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
+  else hipLaunchKernelGGL((calib_fanout<kWG, 2>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
   return (int)hipGetLastError();
 }
 

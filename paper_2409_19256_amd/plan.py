@@ -53,6 +53,15 @@ class Plan:
     def install_own(self, train_ptr: int, gen_ptr: int, stream: int = 0):
         B.check(B.hf_reshard_install_own(self._h, train_ptr, gen_ptr, stream), "hf_reshard_install_own")
 
+    def offload_remote(self, gen_ptr: int, host_ptr: int, stream: int = 0):
+        B.check(B.hf_offload_remote(self._h, gen_ptr, host_ptr, stream), "hf_offload_remote")
+
+    def reload_remote(self, host_ptr: int, gen_ptr: int, stream: int = 0):
+        B.check(B.hf_reload_remote(self._h, host_ptr, gen_ptr, stream), "hf_reload_remote")
+
+    def check_buffers(self, train_ptr: int, train_len: int, gen_ptr: int, gen_len: int):
+        B.check(B.hf_plan_check_buffers(self._h, train_ptr, train_len, gen_ptr, gen_len), "hf_plan_check_buffers")
+
     def gather_responses(self, in_ptr: int, out_ptr: int, slot_bytes: int, stream: int = 0):
         B.check(B.hf_gather_responses(self._h, in_ptr, out_ptr, slot_bytes, stream), "hf_gather_responses")
 
@@ -94,6 +103,13 @@ class Plan:
 
     def rank_gen_offset(self, r: int) -> int:
         return B.hf_plan_rank_gen_offset(self._h, r)
+
+    @property
+    def remote_bytes(self) -> int:
+        return B.hf_plan_remote_bytes(self._h)
+
+    def remote_rank_offset(self, r: int) -> int:
+        return B.hf_plan_remote_rank_offset(self._h, r)
 
     def rank_coords(self, r: int):
         out = (C.c_int32 * 6)()

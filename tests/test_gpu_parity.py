@@ -2,11 +2,14 @@
 bit for bit (the data are opaque 16-bit words: tolerance zero).
 
 Small and medium shapes: whole buffers, element by element, padding included.
-BASELINE shapes 2-5 at full size, in the launch configuration bench.py times: whole
-tensors of sampled (rank, layer) pairs through the oracle's concat/slice code, single
-sampled elements through its element definition, and the count of untouched words
-(own pieces + padding) by a two-canary argument."""
+BASELINE shapes 2-5 at full size, in the launch configuration bench.py times: EVERY tensor
+of EVERY materialised generation rank against the oracle's concat/slice code (streamed
+layer by layer from device memory), every byte between the tensors against a canary, the
+count of words the kernel leaves alone (own pieces + padding) by a two-canary argument,
+and every materialised rank's whole training shard after the reverse path."""
 import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -282,129 +285,278 @@ def test_runtime_argument_errors():
 
 
 # ------------------------------------------------------------------ full-size configs
-def _device_fetch(train_i16):
-    def fetch(off, n):
-        return train_i16[off:off + n].cpu().numpy().view(np.uint16)
-    return fetch
+POOL_THREADS = 12                       # the GPU machine gives one GPU's share of 16 CPUs
 
 
-def _check_full_size(case, cfg_index, sampled_layers, n_elem_samples=400, check_back=False, params=()):
+def _oracle_gen_tensors(orc, ranks, train_i16):
+    """Streams the oracle's generation partition at full size: yields (rank, entry, expected
+    uint16 array [rows, cols]) for EVERY tensor of EVERY rank in `ranks`.  Input of the
+    oracle = the training shards as they sit in device memory, fetched one layer at a time
+    (peak host memory: the full tensors of one layer), concat/slice on a thread pool."""
+    offs = orc.train_region_offsets()
+    for r in range(orc.n_ranks):            # fill the oracle's table caches before threads use them
+        orc.train_table(r)
+        orc.train_entry(r, orc.train_table(r)[0][0].kind, orc.train_table(r)[0][0].layer)
+    for r in ranks:
+        orc.gen_entry(r, orc.gen_table(r)[0][0].kind, orc.gen_table(r)[0][0].layer)
+
+    def group_of(e):
+        return "embed" if e.kind == "embed" else "tail" if e.kind in ("lnf", "head") else e.layer
+
+    with ThreadPoolExecutor(POOL_THREADS) as pool:
+        for grp in ["embed"] + list(range(orc.m.n_layers)) + ["tail"]:
+            store = {}
+            for q in range(orc.n_ranks):
+                for e in orc.train_table(q)[0]:
+                    if group_of(e) == grp:
+                        o = offs[q] + e.offset
+                        store[o] = train_i16[o:o + e.n].cpu().numpy().view(np.uint16)
+
+            def fetch(o, n, store=store):
+                a = store[o]
+                assert a.shape[0] == n
+                return a
+
+            work = [(r, e) for r in ranks for e in orc.gen_table(r)[0] if group_of(e) == grp]
+            wants = pool.map(lambda re: np.ascontiguousarray(orc.gen_tensor(fetch, re[0], re[1].kind, re[1].layer)), work)
+            for (r, e), want in zip(work, wants):
+                assert want.shape == (e.rows, e.cols) and want.dtype == np.uint16
+                yield r, e, want
+
+
+def _to_dev(want):
+    return torch.from_numpy(want.view(np.int16)).cuda()
+
+
+def _equal_chunked(a, b, step=1 << 28):
+    return all(torch.equal(a[c:c + step], b[c:c + step]) for c in range(0, a.numel(), step))
+
+
+def _count_untouched(ar, pl, orc, ranks, gb, gend, label):
+    """Two-canary count: a word the kernel does not write keeps both canaries.  Under
+    SKIP_OWN the kernel must leave alone exactly the own pieces and the padding."""
+    first, untouched = {}, {}
+    for k, canary in enumerate((0x1357, 0x2468)):
+        ar.gen.fill_(_i16(canary))
+        ar.execute()
+        torch.cuda.synchronize()
+        for r in ranks:
+            reg = ar.gen[gb[r]:gend[r]]
+            if k == 0:
+                first[r] = reg == _i16(canary)
+            else:                                   # chunked: reductions over 10^10 words need big temporaries
+                n, step = 0, 1 << 28
+                for c in range(0, reg.numel(), step):
+                    n += int(torch.count_nonzero(first[r][c:c + step] & (reg[c:c + step] == _i16(canary))).item())
+                untouched[r] = n
+    del first
+    for r in ranks:
+        region = gend[r] - gb[r]
+        payload = sum(e.n for e in orc.gen_table(r)[0])
+        own = sum(e.n for e in orc.train_table(r)[0])
+        assert untouched[r] == region - (payload - own), f"{label} rank {r}: wrong number of untouched words"
+
+
+def _check_gaps(gen_region, entries, canary, what):
+    end = 0
+    for e in entries:                               # table order = address order
+        assert bool((gen_region[end:e.offset] == _i16(canary)).all()), (what, e.kind, e.layer)
+        end = e.offset + e.n
+    assert bool((gen_region[end:] == _i16(canary)).all()), what
+
+
+def _check_reverse(ar, orc, ranks, label):
+    """Step 4 at full size: every materialised rank's whole training shard, tensor by
+    tensor, against the bytes it held before (the oracle's round-trip identity:
+    re-partitioning the generation buffers gives back the training shards), and every
+    byte between the tensors against the poison."""
+    offs = orc.train_region_offsets()
+    saved = {r: ar.train[offs[r]:offs[r + 1]].clone() for r in ranks}
+    for r in ranks:
+        ar.train[offs[r]:offs[r + 1]].fill_(_i16(0xBEEF))
+    ar.back()
+    torch.cuda.synchronize()
+    for r in ranks:
+        now = ar.train[offs[r]:offs[r + 1]]
+        end = 0
+        for e in orc.train_table(r)[0]:
+            assert bool((now[end:e.offset] == _i16(0xBEEF)).all()), (label, r, e.kind, e.layer)
+            assert torch.equal(now[e.offset:e.offset + e.n], saved[r][e.offset:e.offset + e.n]), (label, r, e.kind, e.layer)
+            end = e.offset + e.n
+        assert bool((now[end:] == _i16(0xBEEF)).all())
+        now.copy_(saved[r])                         # padding back to what it was
+        del saved[r]
+    _say(f"[{label}] reverse: all {len(ranks)} training shards whole")
+
+
+def _check_full_size_streaming(case, cfg_index):
+    """Configs 3-5: default launch configuration (what bench.py times), every tensor of every
+    materialised rank compared with the oracle while it streams; no cut is made."""
+    t0 = time.perf_counter()
     orc = make_oracle(case)
     ranks = mat_ranks(case, orc)
-    seed = config_seed(cfg_index)
-    rng = np.random.default_rng(cfg_index)
     with make_plan(case, 0) as pl:                         # bench.py's configuration: SKIP_OWN, defaults
-        for k, v in params:
-            pl.set_param(k, v)
         ar = Arena(pl)
+        pl.check_buffers(ar.train_ptr, ar.train.numel() * 2, ar.gen_ptr, ar.gen.numel() * 2)
         _say(f"[{case['name']}] arena {ar.buf.numel() * 2 / 1e9:.1f} GB, W = {pl.bytes_moved(0) / 1e9:.2f} GB; filling inputs")
         ar.train.fill_(_i16(POISON))
-        fill_regions_torch(ar.train, orc.input_regions(tensor_uid), seed)   # regions from the ORACLE's tables
+        fill_regions_torch(ar.train, orc.input_regions(tensor_uid), config_seed(cfg_index))   # regions from the ORACLE's tables
         gb = dict(zip(ranks, orc.gen_region_offsets(ranks)))
         gend = dict(zip(ranks, orc.gen_region_offsets(ranks)[1:]))
-
-        # two-canary count of untouched words: a word untouched in both runs kept both canaries
-        first, untouched = {}, {}
-        for k, canary in enumerate((0x1357, 0x2468)):
-            ar.gen.fill_(_i16(canary))
-            ar.execute()
-            torch.cuda.synchronize()
-            for r in ranks:
-                reg = ar.gen[gb[r]:gend[r]]
-                if k == 0:
-                    first[r] = reg == _i16(canary)
-                else:                                   # chunked: reductions over 10^10 words need big temporaries
-                    n, step = 0, 1 << 28
-                    for c in range(0, reg.numel(), step):
-                        n += int(torch.count_nonzero(first[r][c:c + step] & (reg[c:c + step] == _i16(canary))).item())
-                    untouched[r] = n
-        del first
-        for r in ranks:
-            region = gend[r] - gb[r]
-            payload = sum(e.n for e in orc.gen_table(r)[0])
-            own = sum(e.n for e in orc.train_table(r)[0])
-            # the kernel must write exactly the payload that comes from peers
-            assert untouched[r] == region - (payload - own), f"rank {r}: wrong number of untouched words"
-        _say(f"[{case['name']}] untouched-word counts ok; installing own pieces")
+        _count_untouched(ar, pl, orc, ranks, gb, gend, case["name"])
+        _say(f"[{case['name']}] untouched-word counts ok ({time.perf_counter() - t0:.0f} s); final pass")
+        ar.gen.fill_(_i16(CANARY))
+        ar.execute()
         ar.install_own()
         torch.cuda.synchronize()
-
-        # whole tensors of sampled (rank, layer) pairs through the oracle's concat/slice code
-        fetch = _device_fetch(ar.train)
-        for r, layer in sampled_layers:
-            for e in orc.gen_table(r)[0]:
-                if e.layer != layer:
-                    continue
-                want = orc.gen_tensor(fetch, r, e.kind, e.layer)
-                got = ar.gen[gb[r] + e.offset: gb[r] + e.offset + e.n].cpu().numpy().view(np.uint16).reshape(e.rows, e.cols)
-                assert np.array_equal(got, want), (r, e.kind, e.layer)
-            _say(f"[{case['name']}] rank {r} layer {layer}: all tensors equal the oracle")
-
-        # single elements, one by one, through the element definition
-        names = orc.full_tensor_names()
-        for _ in range(n_elem_samples):
-            name, layer = names[rng.integers(len(names))]
-            rows, cols = orc.full_shape(name)
-            row, col = int(rng.integers(rows)), int(rng.integers(cols))
-            (_, toff), *_ = orc.where_train(0, name, layer, row, col)
-            v = int(ar.train[toff].item())
-            for r, off in orc.where_gen(0, name, layer, row, col):
-                if r in gb:
-                    assert int(ar.gen[gb[r] + off].item()) == v, (name, layer, row, col, r)
-        _say(f"[{case['name']}] {n_elem_samples} sampled elements ok")
-
-        if check_back:
-            offs = orc.train_region_offsets()
-            keep = {}
-            for r in ranks[:2]:
-                keep[r] = ar.train[offs[r]:offs[r + 1]].clone()
-            for r in ranks:
-                ar.train[offs[r]:offs[r + 1]].fill_(_i16(0xBEEF))
-            ar.back()
-            torch.cuda.synchronize()
-            for r, saved in keep.items():
-                now = ar.train[offs[r]:offs[r + 1]]
-                end = 0
-                for e in orc.train_table(r)[0]:          # tensor by tensor; gaps keep the poison
-                    assert bool((now[end:e.offset] == _i16(0xBEEF)).all())
-                    assert torch.equal(now[e.offset:e.offset + e.n], saved[e.offset:e.offset + e.n]), (r, e.kind, e.layer)
-                    end = e.offset + e.n
-                assert bool((now[end:] == _i16(0xBEEF)).all())
-            # sampled single elements of the other ranks: shard value must equal the generation value
-            for _ in range(200):
-                name, layer = names[rng.integers(len(names))]
-                rows, cols = orc.full_shape(name)
-                row, col = int(rng.integers(rows)), int(rng.integers(cols))
-                holders = {r: off for r, off in orc.where_gen(0, name, layer, row, col) if r in gb}
-                for tr, toff in orc.where_train(0, name, layer, row, col):
-                    if tr in holders:
-                        assert int(ar.train[toff].item()) == int(ar.gen[gb[tr] + holders[tr]].item())
-            _say(f"[{case['name']}] reverse ok")
+        n = 0
+        for r, e, want in _oracle_gen_tensors(orc, ranks, ar.train):
+            got = ar.gen[gb[r] + e.offset: gb[r] + e.offset + e.n]
+            assert torch.equal(got, _to_dev(want).reshape(-1)), (case["name"], r, e.kind, e.layer)
+            n += 1
+            if n % 500 == 0:
+                _say(f"[{case['name']}] {n} tensors equal the oracle ({time.perf_counter() - t0:.0f} s)")
+        assert n == sum(len(orc.gen_table(r)[0]) for r in ranks)
+        for r in ranks:
+            _check_gaps(ar.gen[gb[r]:gend[r]], orc.gen_table(r)[0], CANARY, (case["name"], r))
+        _say(f"[{case['name']}] all {n} generation tensors of {len(ranks)} ranks equal the oracle, padding untouched "
+             f"({time.perf_counter() - t0:.0f} s)")
+        _check_reverse(ar, orc, ranks, case["name"])
         del ar
+    torch.cuda.empty_cache()
+    _say(f"[{case['name']}] done in {time.perf_counter() - t0:.0f} s")
+
+
+def test_llama7b_full_size_every_launch_configuration():
+    """Config 2 (the headline workload), whole buffers: the oracle's generation buffers are
+    assembled once in device memory (every tensor from the oracle, canaries between them);
+    then every launch configuration must reproduce that buffer exactly: bench.py's default
+    (SKIP_OWN, cache-blocked list), multicast off and in registers, the persistent-wavefront
+    kernel, the HF_COPY_OWN plan (one-launch full refresh), and a refresh after the training
+    shards changed."""
+    t0 = time.perf_counter()
+    case, cfg_index = BASELINE[1], 1
+    orc = make_oracle(case)
+    ranks = mat_ranks(case, orc)
+    gb = dict(zip(ranks, orc.gen_region_offsets(ranks)))
+    gend = dict(zip(ranks, orc.gen_region_offsets(ranks)[1:]))
+    with make_plan(case, 0) as pl, make_plan(case, B.HF_COPY_OWN) as pl_copy:
+        ar = Arena(pl)
+        pl.check_buffers(ar.train_ptr, ar.train.numel() * 2, ar.gen_ptr, ar.gen.numel() * 2)
+        ar.train.fill_(_i16(POISON))
+        fill_regions_torch(ar.train, orc.input_regions(tensor_uid), config_seed(cfg_index))
+        ref = torch.full_like(ar.gen, _i16(CANARY))
+        n = 0
+        for r, e, want in _oracle_gen_tensors(orc, ranks, ar.train):
+            ref[gb[r] + e.offset: gb[r] + e.offset + e.n].copy_(_to_dev(want).reshape(-1))
+            n += 1
+        assert n == sum(len(orc.gen_table(r)[0]) for r in ranks)
+        _say(f"[llama7b] oracle buffers of {n} tensors assembled on the device ({time.perf_counter() - t0:.0f} s)")
+
+        configs = [("default", []),
+                   ("multicast off", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_OFF)]),
+                   ("multicast in registers", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)]),
+                   ("persistent wavefronts", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED),
+                                              (B.HF_PARAM_VARIANT, B.HF_VARIANT_WAVE_PERSISTENT), (B.HF_PARAM_TILE_BYTES, 16384)])]
+        for label, params in configs:
+            for k, v in params:
+                pl.set_param(k, v)
+            _count_untouched(ar, pl, orc, ranks, gb, gend, label)
+            ar.gen.fill_(_i16(CANARY))
+            ar.execute()
+            ar.install_own()
+            torch.cuda.synchronize()
+            assert _equal_chunked(ar.gen, ref), label
+            _say(f"[llama7b] {label}: whole generation buffers equal the oracle ({time.perf_counter() - t0:.0f} s)")
+        pl.set_param(B.HF_PARAM_VARIANT, B.HF_VARIANT_PARTS)
+        pl.set_param(B.HF_PARAM_TILE_BYTES, 128 * 1024)
+        _check_reverse(ar, orc, ranks, "llama7b")
+
+        # one-launch full refresh (HF_COPY_OWN plan on the same buffers)
+        ar.gen.fill_(_i16(CANARY))
+        pl_copy.execute(ar.train_ptr, ar.gen_ptr, Arena.stream_handle())
+        torch.cuda.synchronize()
+        assert _equal_chunked(ar.gen, ref), "copy_own"
+        _say(f"[llama7b] HF_COPY_OWN: whole generation buffers equal the oracle ({time.perf_counter() - t0:.0f} s)")
+        del ref, ar
     torch.cuda.empty_cache()
 
 
-def test_llama7b_full_size():
-    _check_full_size(BASELINE[1], 1, [(0, 0), (5, 17), (7, 31), (3, -1)], check_back=True)
-
-
-@pytest.mark.parametrize("mode", [B.HF_MULTICAST_OFF, B.HF_MULTICAST_REGISTERS])
-def test_llama7b_full_size_other_multicast_modes(mode):
-    _check_full_size(BASELINE[1], 1, [(2, 9)], n_elem_samples=200, params=[(B.HF_PARAM_MULTICAST, mode)])
-
-
-def test_llama7b_full_size_persistent_wavefront_kernel():
-    _check_full_size(BASELINE[1], 1, [(6, 30)], n_elem_samples=200,
-                     params=[(B.HF_PARAM_VARIANT, B.HF_VARIANT_WAVE_PERSISTENT), (B.HF_PARAM_TILE_BYTES, 16384)])
-
-
 def test_llama13b_full_size_with_reverse():
-    _check_full_size(BASELINE[2], 2, [(0, 0), (6, 20), (7, 39), (1, -1)], check_back=True)
+    _check_full_size_streaming(BASELINE[2], 2)
 
 
 def test_llama34b_gqa_full_size():
-    _check_full_size(BASELINE[3], 3, [(0, 0), (4, 24), (6, 47), (2, -1)], check_back=True)
+    _check_full_size_streaming(BASELINE[3], 3)
 
 
 def test_llama70b_gqa_full_size():
-    _check_full_size(BASELINE[4], 4, [(0, 0), (31, 79), (0, 40), (31, -1)], n_elem_samples=300, check_back=True)
+    _check_full_size_streaming(BASELINE[4], 4)
+
+
+def test_refresh_after_the_training_shards_change():
+    """Freshness contract of the header: train_buf and gen_buf are separate memory.  After the
+    training shards change, a HF_SKIP_OWN execute refreshes the peers' pieces only (the own
+    pieces keep the OLD values until install_own runs); execute + install_own, or one execute
+    of a HF_COPY_OWN plan, gives the complete new generation buffers."""
+    case = MEDIUM[0]
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    old, new = seeded_train_buf(orc, 21), seeded_train_buf(orc, 22)
+    blank = lambda: np.full(orc.gen_region_offsets(ranks)[-1], CANARY, np.uint16)
+    want_old, want_new = orc.reshard(old, blank(), ranks), orc.reshard(new, blank(), ranks)
+    own = _own_mask(orc, ranks)
+    with make_plan(case, 0) as pl, make_plan(case, B.HF_COPY_OWN) as pl_copy:
+        ar = Arena(pl)
+        ar.gen.fill_(_i16(CANARY))
+        ar.train.copy_(torch.from_numpy(old.view(np.int16)))
+        ar.install_own()
+        ar.execute()
+        torch.cuda.synchronize()
+        assert np.array_equal(_d2h(ar.gen), want_old)
+        ar.train.copy_(torch.from_numpy(new.view(np.int16)))      # "the actor was updated"
+        ar.execute()
+        torch.cuda.synchronize()
+        got = _d2h(ar.gen)
+        assert np.array_equal(got[~own], want_new[~own])          # peers' pieces: new
+        assert np.array_equal(got[own], want_old[own])            # own pieces: still the old ones
+        ar.install_own()
+        torch.cuda.synchronize()
+        assert np.array_equal(_d2h(ar.gen), want_new)
+        ar.train.copy_(torch.from_numpy(old.view(np.int16)))      # and back, in one launch
+        pl_copy.execute(ar.train_ptr, ar.gen_ptr, Arena.stream_handle())
+        torch.cuda.synchronize()
+        assert np.array_equal(_d2h(ar.gen), want_old)
+
+
+def test_check_buffers_on_the_device():
+    with make_plan(SMALL[0], 0) as pl:
+        ar = Arena(pl)
+        pl.check_buffers(ar.train_ptr, ar.train.numel() * 2, ar.gen_ptr, ar.gen.numel() * 2)
+        host = np.zeros(1 << 16, np.uint8)
+        p = (host.ctypes.data + 255) // 256 * 256
+        assert B.hf_plan_check_buffers(pl._h, p, pl.train_bytes, ar.gen_ptr, pl.gen_bytes) == B.HF_ERANGE   # not device memory
+        small = torch.empty(1024, dtype=torch.int16, device="cuda")
+        rc = B.hf_plan_check_buffers(pl._h, ar.train_ptr, pl.train_bytes, small.data_ptr(), pl.gen_bytes)
+        assert rc in (B.HF_OK, B.HF_ERANGE)      # torch may carve `small` out of a larger device segment
+        assert B.hf_plan_check_buffers(pl._h, ar.train_ptr, pl.train_bytes, small.data_ptr(), 2048) == B.HF_EINVAL
+
+
+def test_fanout_calibration_kernels_copy_exactly():
+    n = 3 * 65536 + 8192                                   # bytes: several blocks and a ragged one
+    src = torch.randint(-30000, 30000, (n // 2,), dtype=torch.int16, device="cuda")
+    st = Arena.stream_handle()
+    for block, wg in [(0, 1024), (0, 4096), (0, 8192), (65536, 1024), (65536, 4096), (131072, 8192)]:
+        for n_dst in (1, 3):
+            stride = n + 256
+            dst = torch.full((n_dst * stride // 2,), 77, dtype=torch.int16, device="cuda")
+            B.check(B.hf_calib_fanout(src.data_ptr(), dst.data_ptr(), n, n_dst, stride, block, wg, st), "fanout")
+            torch.cuda.synchronize()
+            for j in range(n_dst):
+                assert torch.equal(dst[j * stride // 2: j * stride // 2 + n // 2], src), (block, wg, n_dst, j)
+                assert bool((dst[j * stride // 2 + n // 2: (j + 1) * stride // 2] == 77).all())
+    dst = torch.full((n // 2,), 77, dtype=torch.int16, device="cuda")
+    B.check(B.hf_calib_fanout(None, dst.data_ptr(), n, 1, n, 0, 4096, st), "write only")
+    B.check(B.hf_calib_fanout(src.data_ptr(), None, n, 1, n, 0, 4096, st), "read only")
+    torch.cuda.synchronize()
+    assert bool((dst == 0x5A5A).all())

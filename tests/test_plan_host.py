@@ -25,7 +25,7 @@ CANARY = 0xC0DE
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "hfreshard.h")).read()
     declared = set(re.findall(r"^HF_API[^;(]*?\b(hf_\w+)\s*\(", header, flags=re.M))
-    assert len(declared) >= 29
+    assert len(declared) >= 38
     lib = C.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -291,6 +291,85 @@ def test_baseline_config_descriptors_against_element_definition(idx):
                 assert (d.src_rank, src // 2) in locs, (kind, d.layer, d.dst_rank, d.src_rank)
 
 
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+@pytest.mark.parametrize("use_tiles,tile_bytes", [(False, 128 * 1024), (True, 128 * 1024), (True, 4096)], ids=["descs", "tiles", "tiles4k"])
+def test_interpreted_offload_and_reload_reproduce_the_oracle_image(case, use_tiles, tile_bytes):
+    """hf_offload_remote / hf_reload_remote on the CPU: the library's descriptors and tiles,
+    interpreted as documented, must give the oracle's image of the remote pieces and bring
+    the remote pieces (and nothing else) back."""
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 99)
+    gen = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    _, rank_offsets, total = orc.remote_layout(ranks)
+    want = orc.pack_remote(gen, ranks, np.full(total, CANARY, np.uint16))
+    run = run_tiles if use_tiles else run_descs
+    with make_plan(case, HOST | B.HF_PLAN_OFFLOAD) as pl:
+        pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+        pl.validate()
+        assert pl.remote_bytes == 2 * total
+        assert [pl.remote_rank_offset(r) for r in ranks] == [2 * o for o in rank_offsets]
+        assert pl.bytes_moved(B.HF_DIR_OFFLOAD) == pl.bytes_moved(B.HF_DIR_RELOAD) == pl.bytes_moved(0)
+        items = pl.tiles(B.HF_DIR_OFFLOAD) if use_tiles else pl.descs(B.HF_DIR_OFFLOAD)
+        image = np.full(total, CANARY, np.uint16)
+        run(items, gen.view(np.uint8), image.view(np.uint8))
+        assert np.array_equal(image, want)
+        # reload into a buffer whose remote pieces were lost
+        own = _own_mask(orc, ranks)
+        pay = _payload(orc, ranks)
+        lost = gen.copy()
+        lost[pay & ~own] = 0x0BAD
+        lost[~pay] = CANARY
+        items = pl.tiles(B.HF_DIR_RELOAD) if use_tiles else pl.descs(B.HF_DIR_RELOAD)
+        run(items, image.view(np.uint8), lost.view(np.uint8))
+        assert np.array_equal(lost[pay], gen[pay]) and (lost[~pay] == CANARY).all()
+    with make_plan(case, HOST) as pl:                    # without the flag: descriptors yes, work lists no
+        assert pl.num_desc(B.HF_DIR_OFFLOAD) == pl.num_desc(0) and pl.num_tiles(B.HF_DIR_OFFLOAD) == 0
+
+
+def test_offload_image_of_a_subset_of_ranks_and_entry_point_errors():
+    case = SMALL[3]
+    orc = make_oracle(case)
+    ranks = [9, 0, 14]
+    _, rank_offsets, total = orc.remote_layout(ranks)
+    with make_plan(case, HOST | B.HF_PLAN_OFFLOAD, mat=ranks) as pl:
+        pl.validate()
+        assert pl.remote_bytes == 2 * total
+        assert [pl.remote_rank_offset(r) for r in ranks] == [2 * o for o in rank_offsets]
+        assert pl.remote_rank_offset(1) == 2 ** 64 - 1
+        # a host-only plan refuses to launch
+        assert B.hf_offload_remote(pl._h, 256, 4096, None) == B.HF_EINVAL
+        assert B.hf_reload_remote(pl._h, None, 256, None) == B.HF_EINVAL
+
+
+def test_check_buffers_on_the_host():
+    with make_plan(SMALL[0], HOST) as pl:
+        tb, gb = pl.train_bytes, pl.gen_bytes
+        base = 1 << 20
+        assert B.hf_plan_check_buffers(pl._h, base, tb, base + (1 << 24), gb) == B.HF_OK
+        assert B.hf_plan_check_buffers(pl._h, base, tb - 1, base + (1 << 24), gb) == B.HF_EINVAL
+        assert b"train_buf is shorter" in B.hf_last_error()
+        assert B.hf_plan_check_buffers(pl._h, base, tb, base + (1 << 24), gb - 2) == B.HF_EINVAL
+        assert B.hf_plan_check_buffers(pl._h, base + 2, tb, base + (1 << 24), gb) == B.HF_EINVAL
+        assert B.hf_plan_check_buffers(pl._h, base, tb, base + 256, gb) == B.HF_EINVAL       # overlap
+        assert B.hf_plan_check_buffers(pl._h, None, tb, base, gb) == B.HF_EINVAL
+
+
+def test_kind_restriction_is_a_debug_entry_and_makes_the_plan_invalid():
+    with make_plan(SMALL[0], HOST) as pl:
+        pl.validate()
+        all_bytes = pl.bytes_moved(0)
+        B.check(B.hf_debug_restrict_kinds(pl._h, 1 << B.HF_ROW), "restrict")
+        assert 0 < pl.bytes_moved(0) < all_bytes
+        with pytest.raises(B.HfError):
+            pl.validate()
+        assert B.hf_debug_restrict_kinds(pl._h, 0) == B.HF_EINVAL
+        B.check(B.hf_debug_restrict_kinds(pl._h, 31), "restrict")
+        pl.validate()
+        assert pl.bytes_moved(0) == all_bytes
+        assert pl.set_param.__self__ is pl and B.hf_plan_set_param(pl._h, 7, 3) == B.HF_EINVAL   # the old parameter number is gone
+
+
 def test_error_codes():
     m = dict(n_layers=4, hidden=32, n_q_heads=8, n_kv_heads=4, head_dim=4, ffn=24, vocab=64)
 
@@ -339,6 +418,14 @@ def test_error_codes():
         assert B.hf_calib_copy(None, None, 16, None) == B.HF_EINVAL
         assert B.hf_calib_copy(256, 4096, 24, None) == B.HF_EINVAL
         assert B.hf_calib_copy(256, 512, 1024, None) == B.HF_EINVAL      # overlap
+        assert B.hf_calib_fanout(None, None, 8192, 1, 8192, 0, 4096, None) == B.HF_EINVAL
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 9, 8192, 0, 4096, None) == B.HF_EINVAL     # n_dst
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 4096, 0, 4096, None) == B.HF_EINVAL     # stride < bytes
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 8192, 0, 2048, None) == B.HF_EINVAL     # wg_bytes
+        assert B.hf_calib_fanout(256, 4096, 8192, 1, 8192, 0, 4096, None) == B.HF_EINVAL        # overlap
+        assert B.hf_calib_fanout(256, None, 8192, 1, 8192, 65536, 4096, None) == B.HF_EINVAL    # blocks need both
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_OFFLOAD_WGS, 0)
         d = B.hf_desc()
         assert B.hf_plan_get_desc(pl._h, 0, 10 ** 9, C.byref(d)) == B.HF_ERANGE
         t = B.hf_tensor_info()
