@@ -38,17 +38,15 @@ def measured_traffic(workload, direction, default_config):
     workload and direction (a separate profiling run of the same launch configuration: it is
     NOT measured in this process); (None, None) if there is none or if this run does not use
     the default configuration the counters were taken with."""
-    name = f"hbm_traffic_{workload}{'_back' if direction == 'back' else ''}.txt"
+    name = "hbm_traffic_default_launches.txt"
     path = os.path.join(ROOT, "profiles", name)
     if not default_config or not os.path.exists(path):
         return None, None
-    vals = {}
     for line in open(path):
-        if "=" in line and not line.startswith("#"):
-            k, v = line.split("=")
-            vals[k.strip()] = int(v)
-    total = vals.get("fetch_bytes_per_launch", 0) + vals.get("write_bytes_per_launch", 0)
-    return (total or None), f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run, replayed here)"
+        f = line.split()
+        if len(f) == 5 and f[0] == workload and f[1] == direction:
+            return int(f[2]) + int(f[3]), f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run, replayed here)"
+    return None, None
 
 
 def cpu_baseline(cfg, seconds_target=9.0):
@@ -156,8 +154,8 @@ def measured_ceilings(ar, n_dst, stream):
 
     t, g = ar.train_ptr, ar.gen_ptr
     out = {"unit": "GB/s", "source_bytes": src_bytes,
-           "read_only": timed(fan(t, None, 1, 0, 1024), src_bytes),
-           "write_only": timed(fan(None, g, 1, 0, 1024), src_bytes),
+           "read_only": timed(fan(t, None, 1, 0, 4096), src_bytes),
+           "write_only": timed(fan(None, g, 1, 0, 4096), src_bytes),
            "copy_1_to_1": max(timed(fan(t, g, 1, 0, wg), 2 * src_bytes) for wg in (1024, 4096))}
     if n_dst > 1:
         mix = {f"registers_{wg}B": timed(fan(t, g, n_dst, 0, wg), (1 + n_dst) * src_bytes) for wg in (1024, 4096)}

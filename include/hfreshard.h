@@ -308,8 +308,11 @@ enum {
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for plain streaming lists                */
   HF_PARAM_OFFLOAD_WGS = 10  /* persistent workgroups of hf_offload_remote / hf_reload_remote,
-                                1 .. 4096 (default 256: enough to fill the host link, few
-                                enough to leave the GPU to a reshard on another stream)  */
+                                1 .. 4096.  Default 8: measured, that many keep the host link
+                                as busy as the runtime's copy engine does, while a reshard on
+                                another stream runs at its own speed; hundreds of workgroups
+                                gain nothing on the link and their queued host writes slow
+                                every other kernel's memory traffic by orders of magnitude */
 };
 enum {
   HF_MULTICAST_OFF = 0,       /* one read per destination, destination-major order        */

@@ -229,8 +229,9 @@ static int offload_common(const hf_plan *plan, const void *gen_buf, const void *
   return device_view_of_pinned(host_buf, p.remote_bytes, host_dev);
 }
 
-// The host link, not HBM, bounds these two: a few hundred persistent workgroups keep it
-// full and leave most of the GPU to whatever runs on other streams.
+// The host link, not HBM, bounds these two: a handful of persistent workgroups (each lane
+// with eight 16-byte accesses in flight) keeps it full.  More would only queue host-bound
+// writes in the memory fabric ahead of the HBM traffic of kernels on other streams.
 static int launch_link(const hf::Plan &p, const hf_tile *tiles, size_t n, const void *src, void *dst, void *stream) {
   const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : 0;
   const int e = hf::launch_tiles(tiles, n, nullptr, src, dst, HF_VARIANT_PERSISTENT, (int)p.offload_wgs, policy,
@@ -333,7 +334,7 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
   case HF_PARAM_MULTICAST:
     if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_CACHE_BLOCKED) return fail(HF_EINVAL, "unknown multicast mode");
     p.multicast = value;
-    if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
+      if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
     return HF_OK;
   case HF_PARAM_OFFLOAD_WGS:
     if (value < 1 || value > 4096) return fail(HF_EINVAL, "offload workgroups must be in [1, 4096]");

@@ -83,7 +83,7 @@ struct Plan {
   int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
   int64_t wg_threads = 0; // 0 = chosen per launch
   int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (hf_debug_restrict_kinds)
-  int64_t offload_wgs = 256; // persistent workgroups of the offload / reload kernels
+  int64_t offload_wgs = 8; // persistent workgroups of the offload / reload kernels
   // totals of the descriptors that take part, per direction (set by build_tiles)
   uint64_t moved_bytes[2] = {0, 0}, unique_bytes[2] = {0, 0};
 

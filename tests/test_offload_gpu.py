@@ -50,7 +50,7 @@ def test_offload_image_and_reload_match_oracle(case, ranks):
     for i, r in enumerate(ranks):
         lo, hi = orc.gen_region_offsets(ranks)[i:i + 2]
         lost[lo:hi][(tags[lo:hi] >= 0) & (tags[lo:hi] != r)] = POISON
-    for tile_bytes, wgs in [(128 * 1024, 256), (4096, 3)]:
+    for tile_bytes, wgs in [(128 * 1024, 8), (4096, 300)]:
         _say(f"[offload {case['name']} tile {tile_bytes} workgroups {wgs}]")
         with make_plan(case, B.HF_PLAN_OFFLOAD, mat=ranks) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
