@@ -206,6 +206,21 @@ HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *
 HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up,
+ * tight serving loops, harnesses that forbid hipMalloc): hf_reshard_execute with the work
+ * list staged in a static device array of the library instead of a hipMalloc'ed copy owned by
+ * the plan.  The plan may therefore be built with HF_PLAN_HOST_ONLY (no device memory is ever
+ * allocated for it); train_buf / gen_buf and the result are as for hf_reshard_execute.
+ * The call copies the plan's current train->gen work list into the array on hip_stream (only
+ * if the array does not already hold it) and enqueues the same kernel; it calls no
+ * hipMalloc / hipFree and does not synchronise.  HF_ERANGE if the work list is larger than
+ * HF_STATIC_SCRATCH_BYTES (about 349 000 tiles: the Llama-7B transition fits, the larger
+ * ones need a larger HF_PARAM_TILE_BYTES).  Every GPU holds one such array until the process
+ * ends, and every call on a GPU uses it: calls that overlap on one GPU (different streams,
+ * different plans) race; calls on one stream, or separated by synchronisation, do not. */
+#define HF_STATIC_SCRATCH_BYTES (16u << 20)
+HF_API int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
+
 /* Section 5.2 step 3: all-gather of the generation results inside each micro-DP group.
  * resp_in  (DEVICE, 256-byte aligned): N slots of slot_bytes; slot r holds the results
  *          (prompt + response token ids, any 4-byte-multiple payload) that rank r's

@@ -38,6 +38,7 @@ HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
  HF_PARAM_MC_BLOCK_BYTES) = range(7)
 HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS, HF_PARAM_OFFLOAD_WGS = 8, 9, 10
 HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED = 0, 1, 2
+HF_STATIC_SCRATCH_BYTES = 16 << 20
 HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED, HF_VARIANT_WAVE_PERSISTENT, HF_VARIANT_PARTS = 0, 1, 2, 3, 4
 
 TENSOR_NAMES = {
@@ -92,6 +93,7 @@ SIGNATURES = {
     "hf_reshard_execute": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hf_reshard_back": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hf_reshard_install_own": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hf_reshard_execute_static": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hf_plan_set_param": (C.c_int, [_P, C.c_int, C.c_int64]),
     "hf_plan_get_param": (C.c_int64, [_P, C.c_int]),
     "hf_plan_train_bytes": (C.c_size_t, [_P]),

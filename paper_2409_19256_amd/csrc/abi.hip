@@ -2,7 +2,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -18,7 +20,19 @@ struct hf_plan {
   hf::Plan p;
 };
 
+// Work-list staging area of hf_reshard_execute_static: device memory that exists from the
+// moment the library is loaded, so that the entry point never has to allocate.  In host code
+// this name is only a handle for hipGetSymbolAddress; the address the kernels get is looked
+// up once per device (scratch_of).
+static __device__ __align__(256) unsigned char scratch[HF_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each device
+uint64_t g_scratch_serial[kMaxDevices] = {}; // Plan::serial of the work list staged there
+std::atomic<uint64_t> g_next_serial{1};
 
 thread_local std::string g_err;
 
@@ -109,6 +123,7 @@ int retile(hf::Plan &p, int64_t tile_bytes) {
     (void)hf::build_tiles(p, e2);
     return fail(rc, err);
   }
+  p.serial = g_next_serial++;
   if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload(p);
   return HF_OK;
 }
@@ -164,6 +179,7 @@ int hf_reshard_plan(const hf_model_desc *model, const hf_train_layout *train, co
     rc = HF_ENOMEM;
     err = "out of host memory while building the plan";
   }
+  pl->p.serial = g_next_serial++;
   if (rc == HF_OK && !(gen->flags & HF_PLAN_HOST_ONLY)) {
     rc = upload(pl->p);
     if (rc != HF_OK) err = g_err;
@@ -191,6 +207,54 @@ int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf
     return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, true);
   const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream);
+}
+
+int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
+  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
+  const hf::Plan &p = plan->p;
+  if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
+    return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
+  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
+  if (t0 < g0 + p.gen_bytes && g0 < t0 + p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
+  // the work list hf_reshard_execute would run, from the plan's host copy
+  const int64_t mode = p.effective_multicast();
+  const hf_tile *tiles = mode == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb.data() : mode == HF_MULTICAST_REGISTERS ? p.tiles_fwd_mc.data() : p.tiles_fwd.data();
+  const size_t n = mode == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb.size()
+                   : mode == HF_MULTICAST_REGISTERS   ? p.tiles_fwd_mc.size()
+                   : (p.flags & HF_COPY_OWN)          ? p.tiles_fwd.size()
+                                                      : p.n_tiles_fwd_peer;
+  const size_t tile_bytes = n * sizeof(hf_tile), extra_at = (tile_bytes + 255) / 256 * 256;
+  const size_t extra_bytes = mode == HF_MULTICAST_REGISTERS ? p.mc_dst.size() * sizeof(uint64_t) : 0;
+  if (extra_at + extra_bytes > HF_STATIC_SCRATCH_BYTES)
+    return fail(HF_ERANGE, "work list of " + std::to_string(extra_at + extra_bytes) + " bytes does not fit the static scratch of " +
+                               std::to_string((size_t)HF_STATIC_SCRATCH_BYTES) + " bytes: raise HF_PARAM_TILE_BYTES or use hf_reshard_execute");
+  if (n == 0) return HF_OK;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(HF_EHIP, std::string("no HIP device: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(HF_ERANGE, "device index beyond the library's table");
+  if (p.device >= 0 && dev != p.device) return fail(HF_EINVAL, "the current HIP device is not the one the plan was built on");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char *base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) { // once per device, with that device current
+      void *ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !ptr) return fail(HF_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+      g_scratch_ptr[dev] = ptr;
+    }
+    base = static_cast<char *>(g_scratch_ptr[dev]);
+    if (g_scratch_serial[dev] != p.serial) { // another plan's list (or none) is staged: replace it, in stream order
+      g_scratch_serial[dev] = 0;
+      e = hipMemcpyAsync(base, tiles, tile_bytes, hipMemcpyHostToDevice, st);
+      if (e == hipSuccess && extra_bytes) e = hipMemcpyAsync(base + extra_at, p.mc_dst.data(), extra_bytes, hipMemcpyHostToDevice, st);
+      if (e != hipSuccess) return fail(HF_EHIP, std::string("staging the work list: ") + hipGetErrorString(e));
+      g_scratch_serial[dev] = p.serial;
+    }
+  }
+  return launch(p, reinterpret_cast<const hf_tile *>(base), n, extra_bytes ? reinterpret_cast<const uint64_t *>(base + extra_at) : nullptr,
+                train_buf, gen_buf, hip_stream, mode == HF_MULTICAST_CACHE_BLOCKED);
 }
 
 // host_buf must be pinned host memory; returns the address the device uses for it
@@ -334,7 +398,8 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
   case HF_PARAM_MULTICAST:
     if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_CACHE_BLOCKED) return fail(HF_EINVAL, "unknown multicast mode");
     p.multicast = value;
-      if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
+    p.serial = g_next_serial++;
+    if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
     return HF_OK;
   case HF_PARAM_OFFLOAD_WGS:
     if (value < 1 || value > 4096) return fail(HF_EINVAL, "offload workgroups must be in [1, 4096]");

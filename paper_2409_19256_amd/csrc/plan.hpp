@@ -87,6 +87,10 @@ struct Plan {
   // totals of the descriptors that take part, per direction (set by build_tiles)
   uint64_t moved_bytes[2] = {0, 0}, unique_bytes[2] = {0, 0};
 
+  // changes whenever the work lists change: tells hf_reshard_execute_static whether the list
+  // it staged for this plan is still the current one
+  uint64_t serial = 0;
+
   // device copy (null for HF_PLAN_HOST_ONLY)
   int device = -1;
   // Only the lists the current multicast mode needs are resident: d_tiles_fwd (the whole

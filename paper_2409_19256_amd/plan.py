@@ -47,6 +47,9 @@ class Plan:
     def execute(self, train_ptr: int, gen_ptr: int, stream: int = 0):
         B.check(B.hf_reshard_execute(self._h, train_ptr, gen_ptr, stream), "hf_reshard_execute")
 
+    def execute_static(self, train_ptr: int, gen_ptr: int, stream: int = 0):
+        B.check(B.hf_reshard_execute_static(self._h, train_ptr, gen_ptr, stream), "hf_reshard_execute_static")
+
     def back(self, train_ptr: int, gen_ptr: int, stream: int = 0):
         B.check(B.hf_reshard_back(self._h, train_ptr, gen_ptr, stream), "hf_reshard_back")
 
