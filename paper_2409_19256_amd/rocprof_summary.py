@@ -3,7 +3,9 @@
     python -m paper_2409_19256_amd.rocprof_summary <dir> [--calib-bytes N]
 
 * kernel trace (`rocprofv3 --kernel-trace --stats --output-format csv`): calls, average,
-  min and max duration per kernel, from the per-dispatch trace.
+  min and max duration per kernel and grid size, from the per-dispatch trace (launches of
+  one kernel over different work lists, e.g. the SKIP_OWN and the COPY_OWN transition of
+  one process, have different grids and are listed apart).
 * counters (`rocprofv3 --pmc FETCH_SIZE` or `WRITE_SIZE`, one counter per run): average
   counter value per dispatch of every kernel.  With --calib-bytes N the dispatch of the
   library's `calib_copy` kernel (known to read N and write N bytes) gives the factor that
@@ -29,11 +31,12 @@ def summarise(d: str, calib_bytes: int = 0) -> str:
     if trace:
         dur = collections.defaultdict(list)
         for r in csv.DictReader(open(trace)):
-            dur[r["Kernel_Name"]].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+            grid = "x".join(str(r[c]) for c in sorted(r) if c.startswith("Grid_Size")) or "?"
+            dur[(r["Kernel_Name"], grid)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
         out.append(f"# kernel trace: {os.path.basename(trace)}")
-        out.append(f"{'kernel':72s} {'calls':>6s} {'avg ms':>10s} {'min ms':>10s} {'max ms':>10s} {'total ms':>10s}")
-        for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1]))[:12]:
-            out.append(f"{k[:72]:72s} {len(v):6d} {sum(v)/len(v):10.4f} {min(v):10.4f} {max(v):10.4f} {sum(v):10.3f}")
+        out.append(f"{'kernel':72s} {'grid (threads)':>18s} {'calls':>6s} {'avg ms':>10s} {'min ms':>10s} {'max ms':>10s} {'total ms':>10s}")
+        for (k, g), v in sorted(dur.items(), key=lambda kv: -sum(kv[1]))[:14]:
+            out.append(f"{k[:72]:72s} {g:>18s} {len(v):6d} {sum(v)/len(v):10.4f} {min(v):10.4f} {max(v):10.4f} {sum(v):10.3f}")
     ctr = _find(d, "*counter_collection.csv")
     if ctr:
         val = collections.defaultdict(list)
