@@ -142,8 +142,10 @@ int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) 
 }
 
 // temporal_loads: the work list counts on re-reads being served by L2
+enum { kListTransition = 0, kListFullRefresh = 1, kListOther = 2 }; // names the list in the kernel's name
+
 int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *extra_dst, const void *src, void *dst,
-           void *stream, bool temporal_loads = false) {
+           void *stream, int list_tag, bool temporal_loads = false) {
   // Automatic cache policy, measured on the five benchmark shapes: one-to-one streaming
   // lists gain 2 % from system-scope streaming stores (policy 0); the cache-blocked list
   // loses 8 % with them (they disturb the L2-resident source block) and runs with plain
@@ -157,7 +159,7 @@ int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *ex
   part = threads == 64 ? std::min(part, 8192u) : std::max(part, 4096u);
   const int e = hf::launch_tiles(tiles, n, extra_dst, src, dst, (int)p.variant, (int)p.grid_wgs, policy,
                                  (uint32_t)p.tile_bytes, part,
-                                 (uint32_t)(p.max_wgs_per_launch * (256 / threads)), threads, stream);
+                                 (uint32_t)(p.max_wgs_per_launch * (256 / threads)), threads, list_tag, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
@@ -201,12 +203,13 @@ void hf_plan_destroy(hf_plan *plan) {
 int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
+  const int tag = (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition;
   if (p.effective_multicast() == HF_MULTICAST_REGISTERS)
-    return launch(p, p.d_tiles_fwd_mc, p.tiles_fwd_mc.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream);
+    return launch(p, p.d_tiles_fwd_mc, p.tiles_fwd_mc.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream, tag);
   if (p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED)
-    return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, true);
+    return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, tag, true);
   const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
-  return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream);
+  return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream, tag);
 }
 
 int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
@@ -254,7 +257,7 @@ int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *
     }
   }
   return launch(p, reinterpret_cast<const hf_tile *>(base), n, extra_bytes ? reinterpret_cast<const uint64_t *>(base + extra_at) : nullptr,
-                train_buf, gen_buf, hip_stream, mode == HF_MULTICAST_CACHE_BLOCKED);
+                train_buf, gen_buf, hip_stream, (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition, mode == HF_MULTICAST_CACHE_BLOCKED);
 }
 
 // host_buf must be pinned host memory; returns the address the device uses for it
@@ -299,7 +302,7 @@ static int offload_common(const hf_plan *plan, const void *gen_buf, const void *
 static int launch_link(const hf::Plan &p, const hf_tile *tiles, size_t n, const void *src, void *dst, void *stream) {
   const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : 0;
   const int e = hf::launch_tiles(tiles, n, nullptr, src, dst, HF_VARIANT_PERSISTENT, (int)p.offload_wgs, policy,
-                                 (uint32_t)p.tile_bytes, 4096u, (uint32_t)p.max_wgs_per_launch, 256, stream);
+                                 (uint32_t)p.tile_bytes, 4096u, (uint32_t)p.max_wgs_per_launch, 256, kListOther, stream);
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;
 }
@@ -349,7 +352,7 @@ int hf_plan_check_buffers(const hf_plan *plan, const void *train_buf, size_t tra
 int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
   if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
   const hf::Plan &p = plan->p;
-  return launch(p, p.d_tiles_own, p.tiles_fwd.size() - p.n_tiles_fwd_peer, nullptr, train_buf, gen_buf, hip_stream);
+  return launch(p, p.d_tiles_own, p.tiles_fwd.size() - p.n_tiles_fwd_peer, nullptr, train_buf, gen_buf, hip_stream, kListOther);
 }
 
 int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream) {
@@ -357,7 +360,7 @@ int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, v
   const hf::Plan &p = plan->p;
   if (p.flags & HF_GROUPING_VANILLA)
     return fail(HF_EINVAL, "vanilla grouping keeps the training shard besides the generation buffer: nothing to re-partition");
-  return launch(p, p.d_tiles_back, p.tiles_back.size(), nullptr, gen_buf, train_buf, hip_stream);
+  return launch(p, p.d_tiles_back, p.tiles_back.size(), nullptr, gen_buf, train_buf, hip_stream, kListOther);
 }
 
 int hf_gather_responses(const hf_plan *plan, const void *resp_in, void *resp_out, size_t slot_bytes, void *hip_stream) {

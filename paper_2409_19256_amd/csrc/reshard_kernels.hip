@@ -167,8 +167,11 @@ __global__ __launch_bounds__(kWG) void reshard_one_tile(const hf_tile *__restric
 // out workgroups in index order, so at any moment the chip works on one narrow, moving
 // window of source and destination addresses, and a slow CU simply takes fewer
 // workgroups.  kUnroll = part_bytes / 4 KiB vectors per lane, all loaded before the
-// first store.
-template <int kPolicy, int kUnroll, int kThreads>
+// first store.  kList does not change the code: it names the work list in the kernel's
+// name, so that a profiler's per-kernel statistics keep apart what one process launches
+// over different lists (0 = train->gen without own pieces, 1 = train->gen with own
+// pieces, 2 = any other list: reverse, own pieces alone).
+template <int kPolicy, int kUnroll, int kThreads, int kList>
 __global__ __launch_bounds__(kThreads) void reshard_parts(const hf_tile *__restrict__ tiles, uint32_t n_tiles, uint32_t parts,
                                                           const uint64_t *__restrict__ extra_dst,
                                                           const char *__restrict__ src, char *__restrict__ dst) {
@@ -309,30 +312,39 @@ __global__ __launch_bounds__(kThreads) void calib_fanout(const u32x4 *__restrict
   }
 }
 
+template <int kPolicy, int kList>
+void launch_parts(const hf_tile *d_tiles, uint32_t n, const uint64_t *extra_dst, const char *s, char *d, uint32_t tile_bytes,
+                  uint32_t part_bytes, int wg_threads, hipStream_t st) {
+  const uint32_t parts = (tile_bytes + part_bytes - 1) / part_bytes;
+  const dim3 g(n * parts);
+  if (wg_threads == kWave) { // one wavefront per workgroup: part_bytes = U * 1 KiB
+    switch (part_bytes / 1024) {
+    case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWave, kList>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWave, kList>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWave, kList>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWave, kList>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    }
+  } else {
+    switch (part_bytes / 4096) {
+    case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWG, kList>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWG, kList>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWG, kList>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWG, kList>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
+    }
+  }
+}
+
 template <int kPolicy>
 void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint64_t *extra_dst, const char *s, char *d,
-                   int variant, uint32_t tile_bytes, uint32_t part_bytes, int wg_threads, hipStream_t st) {
+                   int variant, uint32_t tile_bytes, uint32_t part_bytes, int wg_threads, int list_tag, hipStream_t st) {
   switch (variant) {
-  case HF_VARIANT_PARTS: {
-    const uint32_t parts = (tile_bytes + part_bytes - 1) / part_bytes;
-    const dim3 g(n * parts);
-    if (wg_threads == kWave) { // one wavefront per workgroup: part_bytes = U * 1 KiB
-      switch (part_bytes / 1024) {
-      case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWave>), g, dim3(kWave), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      }
-    } else {
-      switch (part_bytes / 4096) {
-      case 1: hipLaunchKernelGGL((reshard_parts<kPolicy, 1, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      case 2: hipLaunchKernelGGL((reshard_parts<kPolicy, 2, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      case 4: hipLaunchKernelGGL((reshard_parts<kPolicy, 4, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      default: hipLaunchKernelGGL((reshard_parts<kPolicy, 8, kWG>), g, dim3(kWG), 0, st, d_tiles, n, parts, extra_dst, s, d); break;
-      }
+  case HF_VARIANT_PARTS:
+    switch (list_tag) {
+    case 0: launch_parts<kPolicy, 0>(d_tiles, n, extra_dst, s, d, tile_bytes, part_bytes, wg_threads, st); break;
+    case 1: launch_parts<kPolicy, 1>(d_tiles, n, extra_dst, s, d, tile_bytes, part_bytes, wg_threads, st); break;
+    default: launch_parts<kPolicy, 2>(d_tiles, n, extra_dst, s, d, tile_bytes, part_bytes, wg_threads, st); break;
     }
     break;
-  }
   case HF_VARIANT_ONE_WG_PER_TILE:
     hipLaunchKernelGGL(reshard_one_tile<kPolicy>, dim3(n), dim3(kWG), 0, st, d_tiles, n, extra_dst, s, d);
     break;
@@ -349,7 +361,7 @@ void launch_policy(const hf_tile *d_tiles, uint32_t n, uint32_t grid, const uint
 
 int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_dst, const void *src, void *dst,
                  int variant, int grid_wgs, int cache_policy, uint32_t tile_bytes, uint32_t part_bytes,
-                 uint32_t max_wgs_per_launch, int wg_threads, void *stream) {
+                 uint32_t max_wgs_per_launch, int wg_threads, int list_tag, void *stream) {
   if (n_tiles == 0) return 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char *s = static_cast<const char *>(src);
@@ -373,12 +385,12 @@ int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_d
       hipLaunchKernelGGL(reshard_persistent_lds, dim3(grid), dim3(kWG), 0, st, t, n, extra_dst, s, d);
     } else {
       switch (cache_policy) {
-      case 1: launch_policy<1>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
-      case 2: launch_policy<2>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
-      case 3: launch_policy<3>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
-      case 4: launch_policy<4>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
-      case 5: launch_policy<5>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
-      default: launch_policy<0>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, st); break;
+      case 1: launch_policy<1>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
+      case 2: launch_policy<2>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
+      case 3: launch_policy<3>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
+      case 4: launch_policy<4>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
+      case 5: launch_policy<5>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
+      default: launch_policy<0>(t, n, grid, extra_dst, s, d, variant, tile_bytes, part_bytes, wg_threads, list_tag, st); break;
       }
     }
     const hipError_t e = hipGetLastError();

@@ -26,12 +26,12 @@ int main() {
       mid{4, 512, 16, 8, 32, 2760, 2000, 2, 0}, l7b{32, 4096, 32, 32, 128, 11008, 32000, 2, 0},
       l70b{80, 8192, 64, 8, 128, 28672, 128256, 2, 0};
   bad += run(tiny, {1, 4, 1}, 1, 2, HF_PLAN_HOST_ONLY, {}, 131072, true);
-  bad += run(tiny, {1, 4, 1}, 1, 2, HF_PLAN_HOST_ONLY | HF_COPY_OWN, {3, 0}, 4096, true);
+  bad += run(tiny, {1, 4, 1}, 1, 2, HF_PLAN_HOST_ONLY | HF_COPY_OWN | HF_PLAN_OFFLOAD, {3, 0}, 4096, true);
   bad += run(odd, {1, 2, 1}, 1, 1, HF_PLAN_HOST_ONLY | HF_COPY_OWN, {}, 4096, true);
-  bad += run(gqa, {4, 4, 2}, 2, 2, HF_PLAN_HOST_ONLY, {}, 8192, true);
+  bad += run(gqa, {4, 4, 2}, 2, 2, HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD, {}, 8192, true);
   bad += run(gqa, {4, 4, 1}, 2, 2, HF_PLAN_HOST_ONLY | HF_GROUPING_VANILLA | HF_COPY_OWN, {}, 8192, true);
-  bad += run(mid, {2, 8, 1}, 1, 2, HF_PLAN_HOST_ONLY, {}, 131072, true);
+  bad += run(mid, {2, 8, 1}, 1, 2, HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD, {}, 131072, true);
   bad += run(l7b, {1, 8, 1}, 1, 2, HF_PLAN_HOST_ONLY, {}, 131072, false); // full validation is O(rows): too slow here
-  bad += run(l70b, {4, 8, 1}, 1, 4, HF_PLAN_HOST_ONLY, {0, 31}, 131072, false);
+  bad += run(l70b, {4, 8, 1}, 1, 4, HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD, {0, 31}, 131072, false);
   return bad ? 1 : 0;
 }

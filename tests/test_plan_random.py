@@ -31,7 +31,7 @@ def cases(draw):
                 gen=GenLayout(pg, tg, grouping), name="random")
     n = p * t * d
     mat = draw(st.one_of(st.none(), st.lists(st.integers(0, n - 1), min_size=1, max_size=min(n, 5), unique=True)))
-    flags = draw(st.sampled_from([0, B.HF_COPY_OWN]))
+    flags = draw(st.sampled_from([0, B.HF_COPY_OWN, B.HF_PLAN_OFFLOAD, B.HF_COPY_OWN | B.HF_PLAN_OFFLOAD]))
     params = dict(tile=draw(st.sampled_from([4096, 8192, 131072])), mc=draw(st.sampled_from([0, 1, 2])),
                   block=draw(st.sampled_from([1 << 20, 2 << 20])), tiles=draw(st.booleans()))
     return case, mat, flags, params
@@ -65,6 +65,22 @@ def test_random_plans_reproduce_oracle(c):
         assert np.array_equal(got[written], want[written])
         assert (got[~written] == POISON).all()
         assert pl.bytes_moved(0) == 2 * int(written.sum())
+        if flags & B.HF_PLAN_OFFLOAD:
+            # the offload image of the remote pieces and its way back (Section 7)
+            _, rank_offsets, total = orc.remote_layout(ranks)
+            assert pl.remote_bytes == 2 * total and [pl.remote_rank_offset(r) for r in ranks] == [2 * o for o in rank_offsets]
+            run = run_tiles if prm["tiles"] else run_descs
+            image = np.full(max(total, 1), 0xABCD, np.uint16)
+            run(pl.tiles(B.HF_DIR_OFFLOAD) if prm["tiles"] else pl.descs(B.HF_DIR_OFFLOAD), want.view(np.uint8), image.view(np.uint8))
+            assert np.array_equal(image, orc.pack_remote(want, ranks, np.full(max(total, 1), 0xABCD, np.uint16)))
+            lost = want.copy()
+            own = np.zeros(src.shape, bool)
+            for i, r in enumerate(ranks):
+                reg = src[gb[i]:gb[i + 1]]
+                own[gb[i]:gb[i + 1]] = (reg >= offs[r]) & (reg < offs[r + 1])
+            lost[(src >= 0) & ~own] = 0x0BAD
+            run(pl.tiles(B.HF_DIR_RELOAD) if prm["tiles"] else pl.descs(B.HF_DIR_RELOAD), image.view(np.uint8), lost.view(np.uint8))
+            assert np.array_equal(lost, want)
         if case["gen"].grouping == "hybridflow":
             # reverse: from complete generation buffers back to the materialised ranks' shards
             back = np.full(train.shape, 0xBEEF, np.uint16)
