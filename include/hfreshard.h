@@ -322,6 +322,11 @@ enum {
   HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for plain streaming lists                */
+  HF_PARAM_ROW_INTERLEAVE = 11, /* 1 (default): the tiles of the column stripes that several
+                                training ranks contribute to one row-parallel generation
+                                tensor (o, down) go out round-robin, so that a destination
+                                row is completed while it is open; 0: stripe after stripe
+                                (re-tiles and re-uploads)                                 */
   HF_PARAM_OFFLOAD_WGS = 10  /* persistent workgroups of hf_offload_remote / hf_reload_remote,
                                 1 .. 4096.  Default 8: measured, that many keep the host link
                                 as busy as the runtime's copy engine does, while a reshard on

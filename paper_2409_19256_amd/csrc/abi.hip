@@ -408,6 +408,10 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     if (value < 1 || value > 4096) return fail(HF_EINVAL, "offload workgroups must be in [1, 4096]");
     p.offload_wgs = value;
     return HF_OK;
+  case HF_PARAM_ROW_INTERLEAVE:
+    if (value != 0 && value != 1) return fail(HF_EINVAL, "row interleave must be 0 or 1");
+    p.row_interleave = value;
+    return retile(p, p.tile_bytes);
   case HF_PARAM_MC_BLOCK_BYTES: {
     if (value < (1 << 20) || value > (1ll << 30)) return fail(HF_EINVAL, "multicast block must be in [1 MiB, 1 GiB]");
     p.mc_block_bytes = value;
@@ -450,6 +454,7 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_MULTICAST: return plan->p.effective_multicast();
   case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
   case HF_PARAM_OFFLOAD_WGS: return plan->p.offload_wgs;
+  case HF_PARAM_ROW_INTERLEAVE: return plan->p.row_interleave;
   case HF_PARAM_WG_THREADS: return plan->p.wg_threads;
   case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;

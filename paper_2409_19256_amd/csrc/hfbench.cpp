@@ -89,7 +89,7 @@ int main(int argc, char **argv) {
   };
   int config = 2, steps = 10, warmup = 3, back = 0, install = 0, graph = 0, offload = 0;
   long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0,
-            wg_threads = 0, resp_tokens = 0, ceilings = 0, offload_wgs = 0;
+            wg_threads = 0, resp_tokens = 0, ceilings = 0, offload_wgs = 0, row_interleave = -1;
   unsigned flags = HF_SKIP_OWN;
   std::vector<int32_t> mat_override;
   for (int i = 1; i < argc; ++i) {
@@ -117,6 +117,7 @@ int main(int argc, char **argv) {
     else if (a == "--graph") graph = 1;
     else if (a == "--offload") { offload = 1; flags |= HF_PLAN_OFFLOAD; }
     else if (a == "--offload-wgs") offload_wgs = val();
+    else if (a == "--row-interleave") row_interleave = val();
     else if (a == "--mat") { // comma-separated ranks to materialise instead of the configuration's
       const std::string list = i + 1 < argc ? argv[++i] : "";
       for (size_t p0 = 0; p0 < list.size();) {
@@ -129,7 +130,7 @@ int main(int argc, char **argv) {
       std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back | --install-own] [--copy-own] [--vanilla] "
                            "[--multicast 0|1|2] [--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] "
                            "[--cache-policy P] [--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--mat r0,r1,..] "
-                           "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]]\n");
+                           "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]] [--row-interleave 0|1]\n");
       return 2;
     }
   }
@@ -151,6 +152,7 @@ int main(int argc, char **argv) {
   if (kind_mask) HF_CHECK(hf_debug_restrict_kinds(plan, (int)kind_mask));
   if (wg_threads) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_WG_THREADS, wg_threads));
   if (offload_wgs) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_OFFLOAD_WGS, offload_wgs));
+  if (row_interleave >= 0) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_ROW_INTERLEAVE, row_interleave));
 
   const size_t tb = hf_plan_train_bytes(plan), gb = hf_plan_gen_bytes(plan);
   const size_t gen_start = (tb + 4095) / 4096 * 4096;

@@ -84,6 +84,7 @@ struct Plan {
   int64_t wg_threads = 0; // 0 = chosen per launch
   int64_t kind_mask = 0x1F; // bit k: descriptors of kind k take part (hf_debug_restrict_kinds)
   int64_t offload_wgs = 8; // persistent workgroups of the offload / reload kernels
+  int64_t row_interleave = 1; // tiles of the column stripes of one row-parallel tensor go out round-robin
   // totals of the descriptors that take part, per direction (set by build_tiles)
   uint64_t moved_bytes[2] = {0, 0}, unique_bytes[2] = {0, 0};
 

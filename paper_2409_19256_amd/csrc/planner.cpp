@@ -452,7 +452,7 @@ int build_tiles(Plan &pl, std::string &err) {
     for (size_t i = 0; i < descs.size();) {
       if (!wanted(descs[i])) { ++i; continue; }
       size_t j = i + 1;
-      if (descs[i].kind == HF_ROW)
+      if (descs[i].kind == HF_ROW && pl.row_interleave)
         while (j < descs.size() && descs[j].kind == HF_ROW && descs[j].dst_rank == descs[i].dst_rank &&
                descs[j].tensor_id == descs[i].tensor_id && descs[j].layer == descs[i].layer)
           ++j;
@@ -552,7 +552,7 @@ int build_tiles(Plan &pl, std::string &err) {
     std::map<SibKey, std::vector<size_t>> siblings;
     for (size_t gi = 0; gi < groups.size(); ++gi) {
       const hf_desc &d0 = *groups[gi][0];
-      if (d0.kind != HF_ROW) continue;
+      if (d0.kind != HF_ROW || !pl.row_interleave) continue;
       const Coords &c = pl.coords[d0.dst_rank];
       siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}].push_back(gi);
     }
@@ -561,7 +561,7 @@ int build_tiles(Plan &pl, std::string &err) {
       if (emitted[gi]) continue;
       const hf_desc &d0 = *groups[gi][0];
       std::vector<size_t> set{gi};
-      if (d0.kind == HF_ROW) {
+      if (d0.kind == HF_ROW && pl.row_interleave) {
         const Coords &c = pl.coords[d0.dst_rank];
         set = siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}];
       }

@@ -166,6 +166,34 @@ def test_own_view_is_where_the_oracle_finds_the_own_shard(case):
             assert int(own.sum()) == sum(e.n for e in orc.train_table(r)[0])
 
 
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[3], BASELINE[0]], ids=lambda c: c["name"])
+def test_row_interleave_only_changes_the_order_of_the_work(case):
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 7)
+    want = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], POISON, np.uint16), ranks)
+    key = lambda t: (t[0].src_off, t[0].rows, t[0].row_bytes, tuple(t[1]))
+    with make_plan(case, HOST | B.HF_COPY_OWN) as pl:
+        lists = {}
+        for ri in (1, 0):
+            pl.set_param(B.HF_PARAM_ROW_INTERLEAVE, ri)
+            assert pl.get_param(B.HF_PARAM_ROW_INTERLEAVE) == ri
+            pl.validate()
+            for mc in (0, 1, 2):
+                pl.set_param(B.HF_PARAM_MULTICAST, mc)
+                tiles = pl.tiles(0)
+                got = np.full(want.shape, POISON, np.uint16)
+                run_tiles(tiles, train.view(np.uint8), got.view(np.uint8))
+                assert np.array_equal(got, want)
+                lists[(ri, mc)] = [key(t) for t in tiles]
+        for mc in (0, 1, 2):
+            assert sorted(lists[(0, mc)]) == sorted(lists[(1, mc)])
+        if orc.a > 1:
+            assert lists[(0, 1)] != lists[(1, 1)]          # with several stripes per tensor the order differs
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_ROW_INTERLEAVE, 2)
+
+
 def test_multicast_tiles_read_every_training_piece_once():
     """Llama-7B TP8->TP2: every training piece is wanted by the d_g-1 = 3 other ranks of
     its micro-DP group, so the multicast list has a third of the tiles, all with 3
