@@ -379,6 +379,76 @@ class ReshardOracle:
                 gen_buf[bases[i] + e.offset: bases[i] + e.offset + e.n] = val.reshape(-1)
         return gen_buf
 
+    # ------------------- step 1 when the training weights live inside the generation buffers
+    # Section 5.3 (last paragraph) and Section 5.4: under the HybridFlow grouping the training
+    # weights of a GPU are a sub-part of its generation weights and are used in place, so the
+    # all-gather of step 1 collects, from every micro-DP peer, the piece that peer trains --
+    # out of the peer's generation buffer.  Same plain definition as above, with another
+    # source: rebuild each full tensor from the pieces the training ranks hold INSIDE THEIR
+    # GENERATION BUFFERS, then slice.
+    def own_piece_from_gen(self, fetch_gen: Callable[[int, int, int], np.ndarray], q: int, name: str, layer: int) -> np.ndarray:
+        """The part of full tensor `name` that rank q trains, read from q's generation buffer.
+
+        fetch_gen(rank, element offset inside that rank's region, n) -> 1-D array.
+        """
+        if self.gl.grouping != "hybridflow":
+            raise ValueError("only the HybridFlow grouping keeps the training shard inside the generation partition")
+        _, _, tp = self.train_coords(q)
+        _, gtp, _ = self.gen_coords(q)
+        kind = {v: k for k, v in self._GEN_TO_FULL.items()}[name]
+        e = self.gen_entry(q, kind, layer)
+        held = np.asarray(fetch_gen(q, e.offset, e.n)).reshape(e.rows, e.cols)
+        if name in REPLICATED:
+            return held
+        rows_full, cols_full = self.full_shape(name)
+        if name in ("wo", "wd"):                       # split along the input dim
+            per_t, per_g = cols_full // self.t, cols_full // self.tg
+            lo = tp * per_t - gtp * per_g              # where the training columns start inside the generation columns
+            assert 0 <= lo and lo + per_t <= per_g
+            return held[:, lo:lo + per_t]
+        per_t, per_g = rows_full // self.t, rows_full // self.tg
+        lo = tp * per_t - gtp * per_g
+        assert 0 <= lo and lo + per_t <= per_g
+        return held[lo:lo + per_t]
+
+    def full_from_own_views(self, fetch_gen, dp: int, name: str, layer: int, take_tp: int = 0) -> np.ndarray:
+        """Rebuild one full logical tensor of replica `dp` from the pieces its t training ranks
+        hold inside their generation buffers (norms: the copy of TP index `take_tp`)."""
+        pp = self._stage_of(name, layer)
+        ranks = [self.rank_of(dp, pp, tp) for tp in range(self.t)]
+        if name in REPLICATED:
+            return self.own_piece_from_gen(fetch_gen, ranks[take_tp], name, layer)
+        axis = 1 if name in ("wo", "wd") else 0
+        return np.concatenate([self.own_piece_from_gen(fetch_gen, q, name, layer) for q in ranks], axis=axis)
+
+    def gather_in_place(self, gen_buf: np.ndarray, mat_ranks: Sequence[int]) -> np.ndarray:
+        """Complete the generation buffers of `mat_ranks` (which hold their own pieces, and
+        anything elsewhere) from each other: every tensor is rebuilt from the own views and
+        sliced.  Needs the generation buffer of every training rank that owns a piece."""
+        bases = self.gen_region_offsets(mat_ranks)
+        pos = {r: i for i, r in enumerate(mat_ranks)}
+        source = gen_buf.copy()                        # all reads see the state before the gather
+
+        def fetch_gen(q, off, n):
+            if q not in pos:
+                raise KeyError(f"generation buffer of rank {q} is not materialised")
+            return source[bases[pos[q]] + off: bases[pos[q]] + off + n]
+
+        for i, r in enumerate(mat_ranks):
+            dp, _, tp = self.train_coords(r)
+            _, gtp, _ = self.gen_coords(r)
+            for e in self.gen_table(r)[0]:
+                name = self._GEN_TO_FULL[e.kind]
+                full = self.full_from_own_views(fetch_gen, dp, name, e.layer, take_tp=tp)
+                if name in REPLICATED:
+                    val = full
+                elif name in ("wo", "wd"):
+                    val = full[:, gtp * e.cols:(gtp + 1) * e.cols]
+                else:
+                    val = full[gtp * e.rows:(gtp + 1) * e.rows]
+                gen_buf[bases[i] + e.offset: bases[i] + e.offset + e.n] = np.ascontiguousarray(val).reshape(-1)
+        return gen_buf
+
     # ----------------------------------------------- step 4: generation -> training
     def full_from_gen(self, fetch_gen: Callable[[int, int, int], np.ndarray], r: int, name: str, layer: int) -> np.ndarray:
         """Rebuild a full tensor from the generation TP group that rank r belongs to.
