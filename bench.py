@@ -4,7 +4,7 @@ one MI355X.  One "step" = one hf_reshard_execute over all materialised generatio
 ranks of the workload, inputs resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--direction fwd|back]
-                    [--flags skip_own|copy_own] [--variant V] [--tile-bytes B] [--grid G]
+                    [--flags skip_own|copy_own] [--from-gen] [--variant V] [--tile-bytes B] [--grid G]
                     [--no-cpu-baseline] [--no-ceilings] [--no-full-refresh]
 """
 import argparse
@@ -180,6 +180,9 @@ def main():
     ap.add_argument("--flags", default="skip_own", choices=["skip_own", "copy_own"])
     ap.add_argument("--grouping", default="hybridflow", choices=["hybridflow", "vanilla"],
                     help="vanilla = the paper's HybridFlow-V generation grouping (Section 5.3)")
+    ap.add_argument("--from-gen", action="store_true",
+                    help="HF_GATHER_FROM_GEN: the peers' pieces are read from the owners' generation buffers (Section 5.3: the "
+                         "training weights are a sub-part of the generation weights), train_buf is not touched")
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--grid", type=int, default=None)
@@ -208,11 +211,13 @@ def main():
         print("bench.py: no GPU visible; the reshard library has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = dict(CONFIGS[args.config], index=args.config)
-    default_config = (args.flags == "skip_own" and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
+    default_config = (args.flags == "skip_own" and not args.from_gen and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
                       and args.grid is None and args.multicast is None and not args.part_bytes and not args.mc_block_bytes)
     flags = B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN
     if args.grouping == "vanilla":
         flags |= B.HF_GROUPING_VANILLA
+    if args.from_gen:
+        flags |= B.HF_GATHER_FROM_GEN
     t0 = time.perf_counter()
     plan = Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags, mat_ranks=cfg["mat"])
     plan_ms = (time.perf_counter() - t0) * 1e3
@@ -265,7 +270,7 @@ def main():
     # not the own view inside gen_buf): the own pieces must be refreshed too.  One launch of a
     # HF_COPY_OWN plan rewrites every byte of every generation buffer.
     full_refresh = None
-    if args.direction == "fwd" and args.flags == "skip_own" and not args.no_full_refresh:
+    if args.direction == "fwd" and args.flags == "skip_own" and not args.no_full_refresh and not args.from_gen:
         with Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags | B.HF_COPY_OWN, mat_ranks=cfg["mat"]) as pc:
             for k, v in ((B.HF_PARAM_MULTICAST, args.multicast), (B.HF_PARAM_PART_BYTES, args.part_bytes),
                          (B.HF_PARAM_MC_BLOCK_BYTES, args.mc_block_bytes), (B.HF_PARAM_TILE_BYTES, args.tile_bytes)):
@@ -302,6 +307,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": cfg["name"], "direction": args.direction, "flags": args.flags, "grouping": args.grouping,
+                   "source_of_peer_pieces": "gen_buf (own views)" if args.from_gen else "train_buf",
                    "ranks": plan.n_ranks, "materialised_gen_ranks": len(plan.mat_ranks), "micro_dp": plan.micro_dp_size,
                    "bytes_written": W, "unique_bytes_read": R, "arena_bytes": ar.buf.numel() * 2,
                    "tile_bytes": plan.get_param(B.HF_PARAM_TILE_BYTES), "grid_wgs": plan.get_param(B.HF_PARAM_GRID_WGS),

@@ -82,6 +82,17 @@ typedef struct {
                                     without a GPU.                                      */
 #define HF_PLAN_OFFLOAD 0x8u     /* also build (and upload) the work lists of
                                     hf_offload_remote / hf_reload_remote                */
+#define HF_GATHER_FROM_GEN 0x10u /* hf_reshard_execute reads every peer's piece from that
+                                    peer's GENERATION buffer (where it is resident as the
+                                    peer's own piece) instead of train_buf: the weights
+                                    then exist once per rank, inside gen_buf, as in the
+                                    paper (Section 5.3: the training weights are a sub-part
+                                    of the generation weights; Section 5.4).  train_buf is
+                                    not touched by execute and may be NULL there; the
+                                    descriptors of direction 0 carry src_off relative to
+                                    gen_buf.  Needs the HybridFlow grouping, HF_SKIP_OWN,
+                                    and every member of the micro-DP group of a materialised
+                                    rank materialised too (HF_EINVAL otherwise).            */
 
 /* Generation sizes p_g-t_g (Section 5.1); the micro-DP size is derived,
  * d_g = p*t/(p_g*t_g).  mat_ranks (host pointer, copied) lists the ranks whose
@@ -201,7 +212,9 @@ HF_API void hf_plan_destroy(hf_plan *plan);
  * either hf_reshard_execute + hf_reshard_install_own on a HF_SKIP_OWN plan, or one
  * hf_reshard_execute on a HF_COPY_OWN plan (one launch, every byte of every generation
  * buffer rewritten).  hf_reshard_execute alone on a HF_SKIP_OWN plan moves exactly the
- * bytes the paper's all-gather moves between GPUs (Section 5.4) and nothing else. */
+ * bytes the paper's all-gather moves between GPUs (Section 5.4) and nothing else.  With
+ * HF_GATHER_FROM_GEN there is no second copy to go stale: the peers' pieces are gathered
+ * from the owners' generation buffers, which is where such a trainer keeps the weights. */
 HF_API int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_back(const hf_plan *plan, void *train_buf, const void *gen_buf, void *hip_stream);
 HF_API int hf_reshard_install_own(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream);

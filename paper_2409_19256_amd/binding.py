@@ -26,7 +26,7 @@ _lib = C.CDLL(LIB_PATH)
 
 # ---- constants (mirror the header) ----------------------------------------------------
 HF_OK, HF_EINVAL, HF_EDIVIS, HF_ERANGE, HF_ENOMEM, HF_EHIP = 0, -1, -2, -3, -4, -5
-HF_SKIP_OWN, HF_COPY_OWN, HF_GROUPING_VANILLA, HF_PLAN_HOST_ONLY, HF_PLAN_OFFLOAD = 0x0, 0x1, 0x2, 0x4, 0x8
+HF_SKIP_OWN, HF_COPY_OWN, HF_GROUPING_VANILLA, HF_PLAN_HOST_ONLY, HF_PLAN_OFFLOAD, HF_GATHER_FROM_GEN = 0x0, 0x1, 0x2, 0x4, 0x8, 0x10
 (HF_T_EMBED, HF_T_LN1, HF_T_QKV, HF_T_O, HF_T_LN2, HF_T_GATE_UP, HF_T_DOWN, HF_T_LNF, HF_T_HEAD) = range(9)
 (HF_G_EMBED, HF_G_LN1, HF_G_Q, HF_G_K, HF_G_V, HF_G_O, HF_G_LN2, HF_G_GATE, HF_G_UP, HF_G_DOWN, HF_G_LNF,
  HF_G_HEAD) = range(16, 28)

@@ -128,16 +128,23 @@ int retile(hf::Plan &p, int64_t tile_bytes) {
   return HF_OK;
 }
 
-int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf) {
-  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
-  if (plan->p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
+// train_optional: the call does not read or write train_buf (it may then be null)
+int check_buffers(const hf::Plan &p, const void *train_buf, const void *gen_buf, bool train_optional) {
+  if (!gen_buf || (!train_buf && !train_optional)) return fail(HF_EINVAL, "null plan or buffer");
   if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
     return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
+  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
+  if (t0 && t0 < g0 + p.gen_bytes && g0 < t0 + p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
+  return HF_OK;
+}
+
+int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf, bool train_optional = false) {
+  if (!plan) return fail(HF_EINVAL, "null plan or buffer");
+  if (int rc = check_buffers(plan->p, train_buf, gen_buf, train_optional)) return rc;
+  if (plan->p.flags & HF_PLAN_HOST_ONLY) return fail(HF_EINVAL, "plan was built with HF_PLAN_HOST_ONLY: it has no device copy");
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev != plan->p.device)
     return fail(HF_EINVAL, "the current HIP device is not the one the plan was built on");
-  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
-  if (t0 < g0 + plan->p.gen_bytes && g0 < t0 + plan->p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
   return HF_OK;
 }
 
@@ -201,7 +208,11 @@ void hf_plan_destroy(hf_plan *plan) {
 }
 
 int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
-  if (int rc = check_exec(plan, train_buf, gen_buf)) return rc;
+  // gathering out of the generation buffers: gen_buf is source and destination (disjoint
+  // pieces), train_buf is not used and need not exist
+  const bool from_gen = plan && (plan->p.flags & HF_GATHER_FROM_GEN);
+  if (int rc = check_exec(plan, train_buf, gen_buf, from_gen)) return rc;
+  if (from_gen) train_buf = gen_buf;
   const hf::Plan &p = plan->p;
   const int tag = (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition;
   if (p.effective_multicast() == HF_MULTICAST_REGISTERS)
@@ -213,12 +224,11 @@ int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf
 }
 
 int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *gen_buf, void *hip_stream) {
-  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
+  if (!plan) return fail(HF_EINVAL, "null plan or buffer");
   const hf::Plan &p = plan->p;
-  if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
-    return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
-  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
-  if (t0 < g0 + p.gen_bytes && g0 < t0 + p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
+  const bool from_gen = (p.flags & HF_GATHER_FROM_GEN) != 0;
+  if (int rc = check_buffers(p, train_buf, gen_buf, from_gen)) return rc;
+  if (from_gen) train_buf = gen_buf; // source and destination are disjoint pieces of gen_buf
   // the work list hf_reshard_execute would run, from the plan's host copy
   const int64_t mode = p.effective_multicast();
   const hf_tile *tiles = mode == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb.data() : mode == HF_MULTICAST_REGISTERS ? p.tiles_fwd_mc.data() : p.tiles_fwd.data();

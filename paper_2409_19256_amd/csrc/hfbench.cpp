@@ -102,6 +102,7 @@ int main(int argc, char **argv) {
     else if (a == "--install-own") install = 1;
     else if (a == "--copy-own") flags |= HF_COPY_OWN;
     else if (a == "--vanilla") flags |= HF_GROUPING_VANILLA;
+    else if (a == "--from-gen") flags |= HF_GATHER_FROM_GEN;
     else if (a == "--multicast") multicast = val();
     else if (a == "--variant") variant = val();
     else if (a == "--tile-bytes") tile_bytes = val();
@@ -127,7 +128,7 @@ int main(int argc, char **argv) {
         p0 = p1 + 1;
       }
     } else {
-      std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back | --install-own] [--copy-own] [--vanilla] "
+      std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back | --install-own] [--copy-own] [--vanilla] [--from-gen] "
                            "[--multicast 0|1|2] [--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] "
                            "[--cache-policy P] [--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--mat r0,r1,..] "
                            "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]] [--row-interleave 0|1]\n");
@@ -202,7 +203,7 @@ int main(int argc, char **argv) {
               "\"algorithmic_bytes\": %.0f, \"ms_mean\": %.4f, \"ms_median\": %.4f, \"ms_min\": %.4f, \"GBps\": %.1f, "
               "\"frac_of_8TBps\": %.4f, \"wall_ms_per_call\": %.4f, \"plan_build_upload_ms\": %.1f}\n",
               c.name, (flags & HF_GROUPING_VANILLA) ? " (vanilla grouping)" : "", back ? "back" : install ? "install_own" : "fwd",
-              (flags & HF_COPY_OWN) ? "copy_own" : "skip_own", mc, (long long)hf_plan_get_param(plan, HF_PARAM_VARIANT),
+              (flags & HF_COPY_OWN) ? "copy_own" : (flags & HF_GATHER_FROM_GEN) ? "skip_own, gathered from gen_buf" : "skip_own", mc, (long long)hf_plan_get_param(plan, HF_PARAM_VARIANT),
               (long long)hf_plan_get_param(plan, HF_PARAM_TILE_BYTES), (long long)hf_plan_get_param(plan, HF_PARAM_PART_BYTES),
               (long long)hf_plan_get_param(plan, HF_PARAM_MC_BLOCK_BYTES), W, R, alg, mean, ms[steps / 2], ms[0], alg / mean / 1e6,
               alg / mean / 1e6 / 8000.0, wall_ms, plan_ms);

@@ -125,6 +125,14 @@ struct Emitter {
     d.dst_block_stride = dbs;
     d.src_row_stride = srs;
     d.dst_row_stride = drs;
+    if ((pl.flags & HF_GATHER_FROM_GEN) && src_rank != dst_rank) {
+      // The peer is a member of the destination's micro-DP group: same generation stage and
+      // TP index, hence the same generation tensors at the same offsets inside its region, and
+      // the piece it trains sits there exactly where it is wanted here.
+      d.src_off = pl.gen_tab[src_rank].base + dst_t.off + dst_delta;
+      d.src_block_stride = dbs;
+      d.src_row_stride = drs;
+    }
     d.flags = desc_align(d) | (src_rank == dst_rank ? HF_DESC_OWN : 0u);
     (src_rank == dst_rank ? pl.fwd_own : pl.fwd_peer).push_back(d);
   }
@@ -153,7 +161,11 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
     if (v <= 0) { err = "all model and layout sizes must be positive"; return HF_EINVAL; }
   if (m.elem_bytes != 2) { err = "elem_bytes must be 2 (bf16)"; return HF_EINVAL; }
   if (m.tied_embed != 0) { err = "tied embedding / LM head is not supported"; return HF_EINVAL; }
-  if (gl.flags & ~(HF_COPY_OWN | HF_GROUPING_VANILLA | HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD)) { err = "unknown flag bits"; return HF_EINVAL; }
+  if (gl.flags & ~(HF_COPY_OWN | HF_GROUPING_VANILLA | HF_PLAN_HOST_ONLY | HF_PLAN_OFFLOAD | HF_GATHER_FROM_GEN)) { err = "unknown flag bits"; return HF_EINVAL; }
+  if ((gl.flags & HF_GATHER_FROM_GEN) && (gl.flags & (HF_COPY_OWN | HF_GROUPING_VANILLA))) {
+    err = "HF_GATHER_FROM_GEN needs the HybridFlow grouping and HF_SKIP_OWN: the own pieces are the source";
+    return HF_EINVAL;
+  }
   if (gl.mat_ranks && gl.n_mat <= 0) { err = "mat_ranks given but n_mat <= 0"; return HF_EINVAL; }
   struct { bool bad; const char *what; } div[] = {
       {tl.tp % gl.tp != 0, "t % t_g"}, {tl.pp % gl.pp != 0, "p % p_g"}, {m.n_layers % tl.pp != 0, "L % p"},
@@ -263,12 +275,14 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
       if (g.id == HF_G_LN1 || g.id == HF_G_LN2 || g.id == HF_G_LNF) {
         // replicated: take the copy of the rank with the same TP index in the owning stage
         const int q = rank_of(spp, c.tp);
+        if ((gl.flags & HF_GATHER_FROM_GEN) && pl.mat_pos[q] < 0) { err = "HF_GATHER_FROM_GEN: a micro-DP peer of a materialised rank is not materialised"; return HF_EINVAL; }
         const int tid = g.id == HF_G_LN1 ? HF_T_LN1 : g.id == HF_G_LN2 ? HF_T_LN2 : HF_T_LNF;
         em.add(q, pl.train_tab[q].at(tid, g.layer), g, HF_REPL, 0, 0, 1, 1, (uint32_t)h2, h2, h2, h2, h2);
         continue;
       }
       for (int k = 0; k < a; ++k) {                    // the a training TP shards inside generation shard gtp
         const int q = rank_of(spp, c.gtp * a + k);
+        if ((gl.flags & HF_GATHER_FROM_GEN) && pl.mat_pos[q] < 0) { err = "HF_GATHER_FROM_GEN: a micro-DP peer of a materialised rank is not materialised"; return HF_EINVAL; }
         const RankTable &st = pl.train_tab[q];
         switch (g.id) {
         case HF_G_EMBED: case HF_G_HEAD: {
@@ -680,6 +694,13 @@ int validate_plan(const Plan &pl, std::string &err) {
     const uint64_t g0 = gt.base + gr.off, g1 = g0 + 2ull * gr.rows * gr.cols;
     const uint64_t s_lo = d.src_off, s_hi = d.src_off + (d.n_blocks - 1) * d.src_block_stride + (d.rows - 1) * d.src_row_stride + d.row_bytes;
     const uint64_t d_lo = d.dst_off, d_hi = d.dst_off + (d.n_blocks - 1) * d.dst_block_stride + (d.rows - 1) * d.dst_row_stride + d.row_bytes;
+    if (forward && (pl.flags & HF_GATHER_FROM_GEN) && d.src_rank != d.dst_rank) {
+      const RankTable &sg = pl.gen_tab[d.src_rank];
+      if (pl.mat_pos[d.src_rank] < 0) return false;
+      const TensorRec &sr = sg.at(d.tensor_id, d.layer);
+      const uint64_t q0 = sg.base + sr.off, q1 = q0 + 2ull * sr.rows * sr.cols;
+      return s_lo >= q0 && s_hi <= q1 && d_lo >= g0 && d_hi <= g1;
+    }
     if (forward) return s_lo >= t0 && s_hi <= t1 && d_lo >= g0 && d_hi <= g1;
     return s_lo >= g0 && s_hi <= g1 && d_lo >= t0 && d_hi <= t1;
   };
@@ -740,6 +761,22 @@ int validate_plan(const Plan &pl, std::string &err) {
   }
   if (!normalise(cb, err, "cache-blocked tiles")) return HF_ERANGE;
   if (!same(cb, mc)) { err = "cache-blocked tiles differ from descriptors"; return HF_ERANGE; }
+  // (3b) gathering out of the generation buffers: every source lies inside an own piece of
+  // its rank (resident, and never a destination of the same launch)
+  if (pl.flags & HF_GATHER_FROM_GEN) {
+    std::vector<Seg> own;
+    for (const hf_desc &d : pl.fwd_own) desc_segments(d, own);
+    for (Seg &s : own) s.src = s.dst;
+    if (!normalise(own, err, "own pieces")) return HF_ERANGE;
+    std::vector<Seg> srcs;
+    for (const hf_desc &d : pl.fwd_peer) desc_segments(d, srcs);
+    for (const Seg &s : srcs) {
+      // last own interval that starts at or before the source segment
+      auto it = std::upper_bound(own.begin(), own.end(), s.src, [](uint64_t v, const Seg &o) { return v < o.dst; });
+      if (it == own.begin() || (--it, s.src + s.len > it->dst + it->len)) { err = "a gather source is not inside an own piece"; return HF_ERANGE; }
+    }
+  }
+
   // (4) offload image: its generation side is exactly the peer destinations, its host side
   // is pairwise disjoint and inside the image; the offload tiles are its descriptors
   {

@@ -139,6 +139,49 @@ def test_whole_buffers_match_oracle(case):
             assert np.array_equal(back[tpay], train[tpay]) and (back[~tpay] == 0xBEEF).all()
 
 
+@pytest.mark.parametrize("case", SMALL + [BASELINE[0]] + MEDIUM, ids=lambda c: c["name"])
+def test_gather_out_of_the_generation_buffers(case):
+    """HF_GATHER_FROM_GEN: every peer's piece is read from that peer's generation buffer.  The
+    buffers start with the own pieces only; train_buf is poisoned (and not even passed) to show
+    that it is not a source; the result must be the oracle's gather_in_place, which is the
+    oracle's reshard of the training shards."""
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 77)
+    complete = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], CANARY, np.uint16), ranks)
+    own = _own_mask(orc, ranks)
+    start = np.full(complete.shape, CANARY, np.uint16)
+    start[own] = complete[own]
+    want = orc.gather_in_place(start.copy(), ranks)
+    assert np.array_equal(want, complete)
+    for variant, tile_bytes, grid, multicast in [VARIANTS[0], VARIANTS[1], VARIANTS[4], VARIANTS[6], VARIANTS[7], VARIANTS[9], VARIANTS[11]]:
+        _say(f"[from-gen {case['name']} variant {variant} tile {tile_bytes} grid {grid} multicast {multicast}]")
+        with make_plan(case, B.HF_GATHER_FROM_GEN) as pl:
+            pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+            if variant == B.HF_VARIANT_PARTS:
+                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))
+                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)
+            else:
+                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
+            pl.set_param(B.HF_PARAM_VARIANT, variant)
+            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+            ar = Arena(pl)
+            ar.train.copy_(torch.from_numpy(train.view(np.int16)))
+            ar.gen.fill_(_i16(CANARY))
+            ar.install_own()                                      # the own pieces, from the training shards, once
+            ar.train.fill_(_i16(0xBEEF))                          # from here on train_buf holds nothing
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), start)
+            pl.execute(None, ar.gen_ptr, Arena.stream_handle())   # no train_buf at all
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want)
+            ar.gen.copy_(torch.from_numpy(start.view(np.int16)))
+            pl.execute_static(None, ar.gen_ptr, Arena.stream_handle())
+            torch.cuda.synchronize()
+            assert np.array_equal(_d2h(ar.gen), want)
+            assert bool((ar.train == _i16(0xBEEF)).all())
+
+
 def test_subset_of_materialised_ranks_and_stream():
     case = MEDIUM[0]
     orc = make_oracle(case)
@@ -432,8 +475,8 @@ def test_llama7b_full_size_every_launch_configuration():
     assembled once in device memory (every tensor from the oracle, canaries between them);
     then every launch configuration must reproduce that buffer exactly: bench.py's default
     (SKIP_OWN, cache-blocked list), multicast off and in registers, the persistent-wavefront
-    kernel, the HF_COPY_OWN plan (one-launch full refresh), and a refresh after the training
-    shards changed."""
+    kernel, the gather out of the generation buffers (HF_GATHER_FROM_GEN) and the HF_COPY_OWN
+    plan (one-launch full refresh)."""
     t0 = time.perf_counter()
     case, cfg_index = BASELINE[1], 1
     orc = make_oracle(case)
@@ -471,6 +514,19 @@ def test_llama7b_full_size_every_launch_configuration():
         pl.set_param(B.HF_PARAM_VARIANT, B.HF_VARIANT_PARTS)
         pl.set_param(B.HF_PARAM_TILE_BYTES, 128 * 1024)
         _check_reverse(ar, orc, ranks, "llama7b")
+
+        # gather out of the generation buffers: own pieces in place, train_buf poisoned and not passed
+        with make_plan(case, B.HF_GATHER_FROM_GEN) as pl_gen:
+            saved_train = ar.train.clone()
+            ar.gen.fill_(_i16(CANARY))
+            ar.install_own()
+            ar.train.fill_(_i16(0xBEEF))
+            pl_gen.execute(None, ar.gen_ptr, Arena.stream_handle())
+            torch.cuda.synchronize()
+            assert _equal_chunked(ar.gen, ref), "gather from gen"
+            ar.train.copy_(saved_train)
+            del saved_train
+            _say(f"[llama7b] HF_GATHER_FROM_GEN: whole generation buffers equal the oracle ({time.perf_counter() - t0:.0f} s)")
 
         # one-launch full refresh (HF_COPY_OWN plan on the same buffers)
         ar.gen.fill_(_i16(CANARY))

@@ -370,6 +370,57 @@ def test_offload_image_of_a_subset_of_ranks_and_entry_point_errors():
         assert B.hf_reload_remote(pl._h, None, 256, None) == B.HF_EINVAL
 
 
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+@pytest.mark.parametrize("use_tiles,multicast", [(False, 2), (True, 0), (True, 1), (True, 2)], ids=["descs", "tiles_mc0", "tiles_mc1", "tiles_mc2"])
+def test_interpreted_gather_out_of_the_generation_buffers(case, use_tiles, multicast):
+    """HF_GATHER_FROM_GEN: the plan reads every peer's piece from that peer's generation buffer.
+    Interpreted on the CPU with gen_buf as source AND destination, starting from buffers that
+    hold only the own pieces, it must give the oracle's gather_in_place."""
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    train = seeded_train_buf(orc, 1234)
+    complete = orc.reshard(train, np.full(orc.gen_region_offsets(ranks)[-1], CANARY, np.uint16), ranks)
+    own = _own_mask(orc, ranks)
+    start = np.full(complete.shape, CANARY, np.uint16)
+    start[own] = complete[own]
+    want = orc.gather_in_place(start.copy(), ranks)
+    assert np.array_equal(want, complete)
+    with make_plan(case, HOST | B.HF_GATHER_FROM_GEN) as pl:
+        pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+        pl.set_param(B.HF_PARAM_TILE_BYTES, 8192)
+        pl.validate()
+        got = start.copy()
+        items = pl.tiles(0) if use_tiles else pl.descs(0)
+        (run_tiles if use_tiles else run_descs)(items, got.view(np.uint8), got.view(np.uint8))
+        assert np.array_equal(got, want)
+        assert pl.bytes_moved(0) == 2 * int((_payload(orc, ranks) & ~own).sum())
+        # same bytes, same sharing as the gather from the training shards
+        with make_plan(case, HOST) as ref:
+            assert pl.bytes_moved(0) == ref.bytes_moved(0) and pl.unique_src_bytes(0) == ref.unique_src_bytes(0)
+            assert pl.num_desc(0) == ref.num_desc(0)
+
+
+def test_gather_from_gen_needs_the_whole_micro_dp_group_and_the_hybridflow_grouping():
+    m = dict(n_layers=4, hidden=32, n_q_heads=8, n_kv_heads=4, head_dim=4, ffn=24, vocab=64)
+
+    def code(flags, mat=None, train=(1, 4, 1), gen=(1, 2)):
+        try:
+            Plan(m, train, gen, flags=HOST | flags, mat_ranks=mat).close()
+            return 0
+        except B.HfError as e:
+            return e.code
+
+    G = B.HF_GATHER_FROM_GEN
+    assert code(G) == 0
+    assert code(G, mat=[0, 1]) == 0                      # one complete micro-DP group
+    assert code(G, mat=[0]) == B.HF_EINVAL               # its peer (rank 1) is missing
+    assert code(G, mat=[0, 2]) == B.HF_EINVAL
+    assert code(G | B.HF_COPY_OWN) == B.HF_EINVAL
+    assert code(G | B.HF_GROUPING_VANILLA) == B.HF_EINVAL
+    assert code(G, mat=[0, 1, 4, 5], train=(2, 4, 1), gen=(1, 2)) == 0   # merged stages: the group spans both stages
+    assert code(G, mat=[0, 1], train=(2, 4, 1), gen=(1, 2)) == B.HF_EINVAL
+
+
 def test_check_buffers_on_the_host():
     with make_plan(SMALL[0], HOST) as pl:
         tb, gb = pl.train_bytes, pl.gen_bytes
