@@ -159,9 +159,10 @@ typedef struct {
   uint32_t rows, row_bytes;
   uint32_t src_row_stride, dst_row_stride;
   uint32_t vec_bytes;    /* 16, 8, 4 or 2: widest access that is aligned everywhere */
-  uint32_t n_dst;        /* >= 1.  Multicast: the source tile is read once and written to
+  uint32_t n_dst;        /* Multicast: the source tile is read once and written to
                             n_dst destinations with the same row stride (one training
-                            piece wanted by several ranks of a micro-DP group)           */
+                            piece wanted by several ranks of a micro-DP group).  0 = a
+                            prefetch tile: loaded and stored nowhere (dst_off unused)    */
   uint32_t dst_list;     /* position of destinations 2..n_dst in the plan's list of extra
                             destination offsets (see hf_plan_get_tile_dst)               */
   uint32_t _pad;
@@ -309,7 +310,9 @@ enum {
   HF_PARAM_VARIANT = 2,      /* HF_VARIANT_*                                              */
   HF_PARAM_MULTICAST = 3,    /* HF_MULTICAST_*: how train->gen serves a training piece that
                                 several ranks of a micro-DP group want.  Same result in
-                                every mode; the modes differ in HBM reads.  When no piece
+                                every mode; the modes differ in HBM reads and in speed.
+                                Default: HF_MULTICAST_CACHE_BLOCKED, and
+                                HF_MULTICAST_PREFETCHED for HF_COPY_OWN plans.  When no piece
                                 of the plan has more than one destination (e.g. only one
                                 rank per micro-DP group is materialised) every mode runs
                                 as HF_MULTICAST_OFF, and hf_plan_get_param says so.      */
@@ -335,6 +338,9 @@ enum {
   HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for plain streaming lists                */
+  HF_PARAM_PREFETCH_BLOCK_BYTES = 12, /* HF_MULTICAST_PREFETCHED: source bytes per block, 1 MiB ..
+                                64 MiB, default 8 MiB: the eight 4 MiB L2s must hold a block
+                                until its copies are done (re-tiles and re-uploads)        */
   HF_PARAM_ROW_INTERLEAVE = 11, /* 1 (default): the tiles of the column stripes that several
                                 training ranks contribute to one row-parallel generation
                                 tensor (o, down) go out round-robin, so that a destination
@@ -351,10 +357,15 @@ enum {
   HF_MULTICAST_OFF = 0,       /* one read per destination, destination-major order        */
   HF_MULTICAST_REGISTERS = 1, /* a workgroup loads a tile once and stores it to every
                                  destination                                             */
-  HF_MULTICAST_CACHE_BLOCKED = 2 /* default: one destination per workgroup, work ordered so
+  HF_MULTICAST_CACHE_BLOCKED = 2, /* one destination per workgroup, work ordered so
                                  that a block of source is copied to destination 1, then
                                  the same block to destination 2, ...; the re-reads are
                                  served by L2 instead of HBM                             */
+  HF_MULTICAST_PREFETCHED = 3 /* as HF_MULTICAST_REGISTERS, but every block of
+                                 HF_PARAM_PREFETCH_BLOCK_BYTES of source is first touched
+                                 by workgroups that only load it (tiles with n_dst == 0),
+                                 so that the workgroups that store it to all destinations
+                                 find it in L2 and spend their life on stores          */
 };
 enum {
   HF_VARIANT_PERSISTENT = 0, /* persistent workgroups stride over the tile list, direct

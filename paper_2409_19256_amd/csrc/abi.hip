@@ -53,6 +53,7 @@ void free_device(hf::Plan &p) {
   release(p.d_tiles_fwd_mc);
   release(p.d_mc_dst);
   release(p.d_tiles_fwd_cb);
+  release(p.d_tiles_fwd_pf);
   release(p.d_tiles_offload);
   release(p.d_tiles_reload);
   release(p.d_micro_peers);
@@ -77,13 +78,12 @@ int upload_forward_lists(hf::Plan &p) {
   int rc = HF_OK;
   if (mode == HF_MULTICAST_OFF) rc = upload_list(p.tiles_fwd.data(), (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer, &p.d_tiles_fwd);
   else release(p.d_tiles_fwd);
-  if (rc == HF_OK && mode == HF_MULTICAST_REGISTERS) {
-    rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
-    if (rc == HF_OK) rc = upload_list(p.mc_dst, &p.d_mc_dst);
-  } else {
-    release(p.d_tiles_fwd_mc);
-    release(p.d_mc_dst);
-  }
+  if (rc == HF_OK && mode == HF_MULTICAST_REGISTERS) rc = upload_list(p.tiles_fwd_mc, &p.d_tiles_fwd_mc);
+  else release(p.d_tiles_fwd_mc);
+  if (rc == HF_OK && mode == HF_MULTICAST_PREFETCHED) rc = upload_list(p.tiles_fwd_pf, &p.d_tiles_fwd_pf);
+  else release(p.d_tiles_fwd_pf);
+  if (rc == HF_OK && p.active_fwd_uses_mc_dst()) rc = upload_list(p.mc_dst, &p.d_mc_dst);
+  else release(p.d_mc_dst);
   if (rc == HF_OK && mode == HF_MULTICAST_CACHE_BLOCKED) rc = upload_list(p.tiles_fwd_cb, &p.d_tiles_fwd_cb);
   else release(p.d_tiles_fwd_cb);
   return rc;
@@ -151,13 +151,21 @@ int check_exec(const hf_plan *plan, const void *train_buf, const void *gen_buf, 
 // temporal_loads: the work list counts on re-reads being served by L2
 enum { kListTransition = 0, kListFullRefresh = 1, kListOther = 2 }; // names the list in the kernel's name
 
+// How a list wants to be run when the plan leaves the choice to the library.
+enum ListShape {
+  kShapeStreaming = 0,  // every byte is read once from HBM
+  kShapeCacheBlocked,   // later passes re-read from L2: plain loads, 8 KiB workgroups
+  kShapePrefetched      // copy workgroups find their source in L2: plain loads, one wavefront per KiB
+};
+
 int launch(const hf::Plan &p, const hf_tile *tiles, size_t n, const uint64_t *extra_dst, const void *src, void *dst,
-           void *stream, int list_tag, bool temporal_loads = false) {
+           void *stream, int list_tag, ListShape shape = kShapeStreaming) {
+  const bool temporal_loads = shape == kShapeCacheBlocked;
   // Automatic cache policy, measured on the five benchmark shapes: one-to-one streaming
   // lists gain 2 % from system-scope streaming stores (policy 0); the cache-blocked list
   // loses 8 % with them (they disturb the L2-resident source block) and runs with plain
   // loads + compiler non-temporal stores (5); multi-destination tiles take 4.
-  const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : temporal_loads ? 5 : extra_dst ? 4 : 0;
+  const int policy = p.cache_policy >= 0 ? (int)p.cache_policy : (temporal_loads || shape == kShapePrefetched) ? 5 : extra_dst ? 4 : 0;
   // Automatic launch shape, measured on the Llama-7B / 34B transitions: lists whose later
   // passes hit L2 run best with 256 lanes x 2 vectors (8 KiB per workgroup); plain streaming
   // lists with one wavefront x 1 vector (1 KiB per workgroup).
@@ -217,8 +225,10 @@ int hf_reshard_execute(const hf_plan *plan, const void *train_buf, void *gen_buf
   const int tag = (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition;
   if (p.effective_multicast() == HF_MULTICAST_REGISTERS)
     return launch(p, p.d_tiles_fwd_mc, p.tiles_fwd_mc.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream, tag);
+  if (p.effective_multicast() == HF_MULTICAST_PREFETCHED)
+    return launch(p, p.d_tiles_fwd_pf, p.tiles_fwd_pf.size(), p.d_mc_dst, train_buf, gen_buf, hip_stream, tag, kShapePrefetched);
   if (p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED)
-    return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, tag, true);
+    return launch(p, p.d_tiles_fwd_cb, p.tiles_fwd_cb.size(), nullptr, train_buf, gen_buf, hip_stream, tag, kShapeCacheBlocked);
   const size_t n = (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
   return launch(p, p.d_tiles_fwd, n, nullptr, train_buf, gen_buf, hip_stream, tag);
 }
@@ -231,13 +241,10 @@ int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *
   if (from_gen) train_buf = gen_buf; // source and destination are disjoint pieces of gen_buf
   // the work list hf_reshard_execute would run, from the plan's host copy
   const int64_t mode = p.effective_multicast();
-  const hf_tile *tiles = mode == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb.data() : mode == HF_MULTICAST_REGISTERS ? p.tiles_fwd_mc.data() : p.tiles_fwd.data();
-  const size_t n = mode == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb.size()
-                   : mode == HF_MULTICAST_REGISTERS   ? p.tiles_fwd_mc.size()
-                   : (p.flags & HF_COPY_OWN)          ? p.tiles_fwd.size()
-                                                      : p.n_tiles_fwd_peer;
+  const hf_tile *tiles = p.active_fwd().data();
+  const size_t n = p.active_fwd_count();
   const size_t tile_bytes = n * sizeof(hf_tile), extra_at = (tile_bytes + 255) / 256 * 256;
-  const size_t extra_bytes = mode == HF_MULTICAST_REGISTERS ? p.mc_dst.size() * sizeof(uint64_t) : 0;
+  const size_t extra_bytes = p.active_fwd_uses_mc_dst() ? p.mc_dst.size() * sizeof(uint64_t) : 0;
   if (extra_at + extra_bytes > HF_STATIC_SCRATCH_BYTES)
     return fail(HF_ERANGE, "work list of " + std::to_string(extra_at + extra_bytes) + " bytes does not fit the static scratch of " +
                                std::to_string((size_t)HF_STATIC_SCRATCH_BYTES) + " bytes: raise HF_PARAM_TILE_BYTES or use hf_reshard_execute");
@@ -267,7 +274,8 @@ int hf_reshard_execute_static(const hf_plan *plan, const void *train_buf, void *
     }
   }
   return launch(p, reinterpret_cast<const hf_tile *>(base), n, extra_bytes ? reinterpret_cast<const uint64_t *>(base + extra_at) : nullptr,
-                train_buf, gen_buf, hip_stream, (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition, mode == HF_MULTICAST_CACHE_BLOCKED);
+                train_buf, gen_buf, hip_stream, (p.flags & HF_COPY_OWN) ? kListFullRefresh : kListTransition,
+                mode == HF_MULTICAST_CACHE_BLOCKED ? kShapeCacheBlocked : mode == HF_MULTICAST_PREFETCHED ? kShapePrefetched : kShapeStreaming);
 }
 
 // host_buf must be pinned host memory; returns the address the device uses for it
@@ -409,7 +417,7 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     p.variant = value;
     return HF_OK;
   case HF_PARAM_MULTICAST:
-    if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_CACHE_BLOCKED) return fail(HF_EINVAL, "unknown multicast mode");
+    if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_PREFETCHED) return fail(HF_EINVAL, "unknown multicast mode");
     p.multicast = value;
     p.serial = g_next_serial++;
     if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
@@ -418,6 +426,10 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     if (value < 1 || value > 4096) return fail(HF_EINVAL, "offload workgroups must be in [1, 4096]");
     p.offload_wgs = value;
     return HF_OK;
+  case HF_PARAM_PREFETCH_BLOCK_BYTES:
+    if (value < (1 << 20) || value > (64 << 20)) return fail(HF_EINVAL, "prefetch block must be in [1 MiB, 64 MiB]");
+    p.prefetch_block_bytes = value;
+    return retile(p, p.tile_bytes);
   case HF_PARAM_ROW_INTERLEAVE:
     if (value != 0 && value != 1) return fail(HF_EINVAL, "row interleave must be 0 or 1");
     p.row_interleave = value;
@@ -465,6 +477,7 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_MC_BLOCK_BYTES: return plan->p.mc_block_bytes;
   case HF_PARAM_OFFLOAD_WGS: return plan->p.offload_wgs;
   case HF_PARAM_ROW_INTERLEAVE: return plan->p.row_interleave;
+  case HF_PARAM_PREFETCH_BLOCK_BYTES: return plan->p.prefetch_block_bytes;
   case HF_PARAM_WG_THREADS: return plan->p.wg_threads;
   case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;
@@ -600,9 +613,7 @@ int hf_plan_get_own_view(const hf_plan *plan, int rank, size_t i, hf_desc *out) 
 size_t hf_plan_num_tiles(const hf_plan *plan, int direction) {
   if (!plan) return 0;
   const hf::Plan &p = plan->p;
-  if (direction == HF_DIR_TRAIN_TO_GEN && p.effective_multicast() == HF_MULTICAST_REGISTERS) return p.tiles_fwd_mc.size();
-  if (direction == HF_DIR_TRAIN_TO_GEN && p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED) return p.tiles_fwd_cb.size();
-  if (direction == HF_DIR_TRAIN_TO_GEN) return (p.flags & HF_COPY_OWN) ? p.tiles_fwd.size() : p.n_tiles_fwd_peer;
+  if (direction == HF_DIR_TRAIN_TO_GEN) return p.active_fwd_count();
   if (direction == HF_DIR_GEN_TO_TRAIN) return p.tiles_back.size();
   if (direction == HF_DIR_OFFLOAD) return p.tiles_offload.size();
   if (direction == HF_DIR_RELOAD) return p.tiles_reload.size();
@@ -616,9 +627,7 @@ int hf_plan_get_tile(const hf_plan *plan, int direction, size_t i, hf_tile *out)
   *out = direction == HF_DIR_GEN_TO_TRAIN                    ? p.tiles_back[i]
          : direction == HF_DIR_OFFLOAD                           ? p.tiles_offload[i]
          : direction == HF_DIR_RELOAD                            ? p.tiles_reload[i]
-         : p.effective_multicast() == HF_MULTICAST_REGISTERS     ? p.tiles_fwd_mc[i]
-         : p.effective_multicast() == HF_MULTICAST_CACHE_BLOCKED ? p.tiles_fwd_cb[i]
-                                                              : p.tiles_fwd[i];
+                                                                 : p.active_fwd()[i];
   return HF_OK;
 }
 

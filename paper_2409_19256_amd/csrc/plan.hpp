@@ -66,18 +66,37 @@ struct Plan {
   std::vector<uint64_t> mc_dst;
   // the same work, one destination per tile, in cache-blocked order (see build_tiles)
   std::vector<hf_tile> tiles_fwd_cb;
+  // the multicast list with a prefetch tile (n_dst == 0: loaded, stored nowhere) for every tile,
+  // block-wise in front of the tiles themselves (see build_tiles)
+  std::vector<hf_tile> tiles_fwd_pf;
   // offload / reload work lists (only with HF_PLAN_OFFLOAD): gen_buf -> image and back
   std::vector<hf_tile> tiles_offload, tiles_reload;
   bool has_sharing = false; // some training piece has more than one destination
   // multicast mode that execute really uses: without sharing the multicast lists are the
   // one-destination work in another order, and the plain list with streaming loads is faster
   int64_t effective_multicast() const { return has_sharing ? multicast : (int64_t)HF_MULTICAST_OFF; }
+  // host copy of the work list hf_reshard_execute runs in the current mode, and its length
+  const std::vector<hf_tile> &active_fwd() const {
+    switch (effective_multicast()) {
+    case HF_MULTICAST_REGISTERS: return tiles_fwd_mc;
+    case HF_MULTICAST_CACHE_BLOCKED: return tiles_fwd_cb;
+    case HF_MULTICAST_PREFETCHED: return tiles_fwd_pf;
+    default: return tiles_fwd;
+    }
+  }
+  size_t active_fwd_count() const {
+    return effective_multicast() == HF_MULTICAST_OFF && !(flags & HF_COPY_OWN) ? n_tiles_fwd_peer : active_fwd().size();
+  }
+  bool active_fwd_uses_mc_dst() const {
+    return effective_multicast() == HF_MULTICAST_REGISTERS || effective_multicast() == HF_MULTICAST_PREFETCHED;
+  }
 
   int64_t tile_bytes = 128 * 1024;
   int64_t grid_wgs = 2048;
   int64_t variant = HF_VARIANT_PARTS;
   int64_t multicast = HF_MULTICAST_CACHE_BLOCKED;
   int64_t mc_block_bytes = 2 << 20;
+  int64_t prefetch_block_bytes = 8 << 20;
   int64_t cache_policy = -1; // auto
   int64_t part_bytes = 0; // 0 = chosen per launch
   int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
@@ -96,13 +115,15 @@ struct Plan {
   int device = -1;
   // Only the lists the current multicast mode needs are resident: d_tiles_fwd (the whole
   // one-destination list) for HF_MULTICAST_OFF, d_tiles_fwd_mc + d_mc_dst for
-  // HF_MULTICAST_REGISTERS, d_tiles_fwd_cb for HF_MULTICAST_CACHE_BLOCKED; the own tiles
+  // HF_MULTICAST_REGISTERS, d_tiles_fwd_cb for HF_MULTICAST_CACHE_BLOCKED, d_tiles_fwd_pf +
+  // d_mc_dst for HF_MULTICAST_PREFETCHED; the own tiles
   // (hf_reshard_install_own), the reverse list and the group table always.
   hf_tile *d_tiles_fwd = nullptr;
   hf_tile *d_tiles_own = nullptr;
   hf_tile *d_tiles_back = nullptr;
   hf_tile *d_tiles_fwd_mc = nullptr;
   hf_tile *d_tiles_fwd_cb = nullptr;
+  hf_tile *d_tiles_fwd_pf = nullptr;
   hf_tile *d_tiles_offload = nullptr;
   hf_tile *d_tiles_reload = nullptr;
   uint64_t *d_mc_dst = nullptr;

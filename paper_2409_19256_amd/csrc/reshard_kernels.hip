@@ -65,11 +65,19 @@ template <typename V, int kPolicy> __device__ __forceinline__ void store_stream(
   }
 }
 
+// a loaded value is "used" without any store: an empty instruction sequence that takes
+// its registers as inputs keeps the load from being optimised away
+__device__ __forceinline__ void keep_alive(const u32x4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+__device__ __forceinline__ void keep_alive(const u32x2 &v) { asm volatile("" : : "v"(v.x), "v"(v.y)); }
+__device__ __forceinline__ void keep_alive(uint32_t v) { asm volatile("" : : "v"(v)); }
+__device__ __forceinline__ void keep_alive(uint16_t v) { asm volatile("" : : "v"((uint32_t)v)); }
+
 // rows x row_bytes, byte (row, i) at base + row*stride + i on either side, copied by a
 // group of kGroup consecutive lanes (a workgroup or one wavefront); `lane` is the index
 // inside the group.  Vector index v in [0, rows*vpr) maps to row = v / vpr, column =
 // v % vpr, so the lanes of a wavefront walk consecutive bytes of a row and spill into
-// the next row at its end.  The loaded vectors are stored to n_dst destinations.
+// the next row at its end.  The loaded vectors are stored to n_dst destinations; a tile
+// with n_dst == 0 is only loaded (it brings its source into L2 for a later tile).
 // `part`/`part_bytes`: the group copies only bytes [part*part_bytes, (part+1)*part_bytes)
 // of the tile's payload (part_bytes == 0: the whole tile).
 template <typename V, int kGroup, int kPolicy, int kUnroll>
@@ -100,6 +108,12 @@ __device__ __forceinline__ void copy_tile(const hf_tile &tl, const uint64_t *__r
         doff[k] = row * dstr + col;
       }
       if (i < total) v[k] = load_stream<V, kPolicy>(src + soff);
+    }
+    if (tl.n_dst == 0) { // uniform
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k)
+        if (i0 + k * kGroup < total) keep_alive(v[k]);
+      continue;
     }
     for (uint32_t j = 0; j < tl.n_dst; ++j) { // uniform trip count
       char *__restrict__ dst = dst_base + (j == 0 ? tl.dst_off : extra_dst[tl.dst_list + j - 1]);
@@ -246,10 +260,6 @@ __global__ __launch_bounds__(kWG) void gather_slots(const int32_t *__restrict__ 
   const uint64_t i = (uint64_t)chunk * kWG + threadIdx.x;
   if (i < slot_vecs) out[(uint64_t)pair * slot_vecs + i] = in[(uint64_t)peers[pair] * slot_vecs + i];
 }
-
-// a loaded vector is "used" without any store: an empty instruction sequence that takes
-// the four registers as inputs keeps the loads from being optimised away
-__device__ __forceinline__ void keep_alive(const u32x4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
 
 // read-only and write-only counterparts of calib_copy (ceilings of one direction)
 __global__ __launch_bounds__(kWG) void calib_read(const u32x4 *__restrict__ src, size_t n_vec) {

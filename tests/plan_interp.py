@@ -16,7 +16,11 @@ def run_descs(descs, src_u8: np.ndarray, dst_u8: np.ndarray) -> None:
 def run_tiles(tiles, src_u8: np.ndarray, dst_u8: np.ndarray) -> None:
     """tiles: [(hf_tile, [destination offsets])] as Plan.tiles() returns them."""
     for tl, dsts in tiles:
-        assert len(dsts) == tl.n_dst >= 1 and dsts[0] == tl.dst_off
+        assert len(dsts) == tl.n_dst
+        if tl.n_dst == 0:          # a prefetch tile: read, written nowhere; the source must exist
+            assert tl.src_off + (tl.rows - 1) * tl.src_row_stride + tl.row_bytes <= src_u8.shape[0]
+            continue
+        assert dsts[0] == tl.dst_off
         for r in range(tl.rows):
             s = tl.src_off + r * tl.src_row_stride
             for d in dsts:

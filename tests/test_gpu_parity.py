@@ -73,7 +73,8 @@ VARIANTS = [(B.HF_VARIANT_PERSISTENT, 128 * 1024, 2048, 1), (B.HF_VARIANT_PERSIS
             (B.HF_VARIANT_PARTS, 32 * 1024, 4096, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 16384, 0),
             (B.HF_VARIANT_PARTS, 12288, 8192, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 4096, 2),
             (B.HF_VARIANT_PERSISTENT, 64 * 1024, 1024, 2), (B.HF_VARIANT_PARTS, 64 * 1024, -2048, 2),
-            (B.HF_VARIANT_PARTS, 16 * 1024, -1024, 1)]
+            (B.HF_VARIANT_PARTS, 16 * 1024, -1024, 1), (B.HF_VARIANT_PARTS, 128 * 1024, -1024, 3),
+            (B.HF_VARIANT_PERSISTENT, 32 * 1024, 64, 3), (B.HF_VARIANT_PARTS, 8192, 4096, 3)]
 
 
 @pytest.mark.parametrize("case", SMALL + [BASELINE[0]] + MEDIUM, ids=lambda c: c["name"])
@@ -100,6 +101,8 @@ def test_whole_buffers_match_oracle(case):
             pl.set_param(B.HF_PARAM_MULTICAST, multicast)
             if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
                 pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
+            if multicast == B.HF_MULTICAST_PREFETCHED:
+                pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 1 << 20)
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
             ar.gen.fill_(_i16(POISON))
@@ -119,6 +122,8 @@ def test_whole_buffers_match_oracle(case):
             pl.set_param(B.HF_PARAM_MULTICAST, multicast)
             if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
                 pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
+            if multicast == B.HF_MULTICAST_PREFETCHED:
+                pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 1 << 20)
             assert pl.bytes_moved(0) == 2 * int(remote.sum())
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
@@ -154,7 +159,7 @@ def test_gather_out_of_the_generation_buffers(case):
     start[own] = complete[own]
     want = orc.gather_in_place(start.copy(), ranks)
     assert np.array_equal(want, complete)
-    for variant, tile_bytes, grid, multicast in [VARIANTS[0], VARIANTS[1], VARIANTS[4], VARIANTS[6], VARIANTS[7], VARIANTS[9], VARIANTS[11]]:
+    for variant, tile_bytes, grid, multicast in [VARIANTS[0], VARIANTS[1], VARIANTS[4], VARIANTS[6], VARIANTS[7], VARIANTS[9], VARIANTS[11], VARIANTS[13]]:
         _say(f"[from-gen {case['name']} variant {variant} tile {tile_bytes} grid {grid} multicast {multicast}]")
         with make_plan(case, B.HF_GATHER_FROM_GEN) as pl:
             pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
@@ -499,6 +504,7 @@ def test_llama7b_full_size_every_launch_configuration():
         configs = [("default", []),
                    ("multicast off", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_OFF)]),
                    ("multicast in registers", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)]),
+                   ("multicast in registers, prefetched", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED)]),
                    ("persistent wavefronts", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED),
                                               (B.HF_PARAM_VARIANT, B.HF_VARIANT_WAVE_PERSISTENT), (B.HF_PARAM_TILE_BYTES, 16384)])]
         for label, params in configs:

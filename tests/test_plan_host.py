@@ -77,7 +77,7 @@ def _own_mask(orc, ranks):
 
 @pytest.mark.parametrize("case", CASES, ids=IDS)
 @pytest.mark.parametrize("use_tiles", [False, True], ids=["descs", "tiles"])
-@pytest.mark.parametrize("tile_bytes,multicast", [(128 * 1024, 2), (128 * 1024, 1), (4096, 1), (4096, 0), (8192, 2)])
+@pytest.mark.parametrize("tile_bytes,multicast", [(128 * 1024, 2), (128 * 1024, 1), (4096, 1), (4096, 0), (8192, 2), (4096, 3), (128 * 1024, 3)])
 def test_interpreted_plan_reproduces_oracle(case, use_tiles, tile_bytes, multicast):
     orc = make_oracle(case)
     ranks = list(range(orc.n_ranks))
@@ -179,14 +179,14 @@ def test_row_interleave_only_changes_the_order_of_the_work(case):
             pl.set_param(B.HF_PARAM_ROW_INTERLEAVE, ri)
             assert pl.get_param(B.HF_PARAM_ROW_INTERLEAVE) == ri
             pl.validate()
-            for mc in (0, 1, 2):
+            for mc in (0, 1, 2, 3):
                 pl.set_param(B.HF_PARAM_MULTICAST, mc)
                 tiles = pl.tiles(0)
                 got = np.full(want.shape, POISON, np.uint16)
                 run_tiles(tiles, train.view(np.uint8), got.view(np.uint8))
                 assert np.array_equal(got, want)
                 lists[(ri, mc)] = [key(t) for t in tiles]
-        for mc in (0, 1, 2):
+        for mc in (0, 1, 2, 3):
             assert sorted(lists[(0, mc)]) == sorted(lists[(1, mc)])
         if orc.a > 1:
             assert lists[(0, 1)] != lists[(1, 1)]          # with several stripes per tensor the order differs
@@ -216,6 +216,46 @@ def test_multicast_tiles_read_every_training_piece_once():
             assert src_bytes == pl.unique_src_bytes(0) and dst_bytes == pl.bytes_moved(0)
             pl.set_param(B.HF_PARAM_MULTICAST, 0)
             assert pl.num_tiles(0) == (n - singles) * n_dst + singles
+
+
+def test_prefetched_order_touches_each_block_before_it_is_copied():
+    """HF_MULTICAST_PREFETCHED on Llama-7B TP8->TP2: blocks of at most 8 MiB of source; every block
+    starts with one destination-less tile per shared tile, with the same source geometry and in
+    the same order as the copy tiles that follow; a prefetch tile and its copy tile are a whole
+    number of tiles apart (same XCD for every part)."""
+    with make_plan(BASELINE[1], HOST) as pl:
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED)
+        block = pl.get_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES)
+        assert block == 8 << 20
+        t = B.hf_tile()
+
+        def tile(i):
+            B.check(B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)), "get_tile")
+            return (t.src_off, t.rows, t.row_bytes, t.src_row_stride, t.vec_bytes), t.n_dst, t.rows * t.row_bytes
+
+        n = pl.num_tiles(0)
+        i = blocks = copies = 0
+        while i < min(n, 30000):
+            pre = []
+            while tile(i)[1] == 0:
+                pre.append(tile(i)[0])
+                i += 1
+            assert pre, "a block starts with its prefetch tiles"
+            shared, size = [], 0
+            while i < n and tile(i)[1] != 0:
+                geo, n_dst, nbytes = tile(i)
+                if n_dst > 1:
+                    shared.append(geo)
+                size += nbytes
+                copies += 1
+                i += 1
+            assert shared == pre and size <= block
+            blocks += 1
+        assert blocks > 5
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)
+        assert pl.num_tiles(0) < n
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 4096)
 
 
 def test_cache_blocked_order_repeats_each_source_block_per_destination():
@@ -371,7 +411,7 @@ def test_offload_image_of_a_subset_of_ranks_and_entry_point_errors():
 
 
 @pytest.mark.parametrize("case", CASES, ids=IDS)
-@pytest.mark.parametrize("use_tiles,multicast", [(False, 2), (True, 0), (True, 1), (True, 2)], ids=["descs", "tiles_mc0", "tiles_mc1", "tiles_mc2"])
+@pytest.mark.parametrize("use_tiles,multicast", [(False, 2), (True, 0), (True, 1), (True, 2), (True, 3)], ids=["descs", "tiles_mc0", "tiles_mc1", "tiles_mc2", "tiles_mc3"])
 def test_interpreted_gather_out_of_the_generation_buffers(case, use_tiles, multicast):
     """HF_GATHER_FROM_GEN: the plan reads every peer's piece from that peer's generation buffer.
     Interpreted on the CPU with gen_buf as source AND destination, starting from buffers that
@@ -487,7 +527,7 @@ def test_error_codes():
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_VARIANT, 9)
         with pytest.raises(B.HfError):
-            pl.set_param(B.HF_PARAM_MULTICAST, 3)
+            pl.set_param(B.HF_PARAM_MULTICAST, 4)
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_CACHE_POLICY, 6)
         with pytest.raises(B.HfError):

@@ -32,7 +32,7 @@ def cases(draw):
     n = p * t * d
     mat = draw(st.one_of(st.none(), st.lists(st.integers(0, n - 1), min_size=1, max_size=min(n, 5), unique=True)))
     flags = draw(st.sampled_from([0, B.HF_COPY_OWN, B.HF_PLAN_OFFLOAD, B.HF_COPY_OWN | B.HF_PLAN_OFFLOAD]))
-    params = dict(tile=draw(st.sampled_from([4096, 8192, 131072])), mc=draw(st.sampled_from([0, 1, 2])),
+    params = dict(tile=draw(st.sampled_from([4096, 8192, 131072])), mc=draw(st.sampled_from([0, 1, 2, 3])),
                   block=draw(st.sampled_from([1 << 20, 2 << 20])), tiles=draw(st.booleans()))
     return case, mat, flags, params
 

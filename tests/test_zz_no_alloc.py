@@ -36,7 +36,7 @@ def test_static_entry_point_matches_execute_on_two_calls_in_a_row():
     st = Arena.stream_handle()
     # first a medium shape in every multicast mode and both flag settings, then smaller shapes:
     # every call after the first finds another plan's work list in the array
-    runs = [(MEDIUM[0], B.HF_COPY_OWN, m) for m in (2, 1, 0)] + [(MEDIUM[0], 0, 2), (SMALL[3], B.HF_COPY_OWN, 2),
+    runs = [(MEDIUM[0], B.HF_COPY_OWN, m) for m in (2, 1, 0, 3)] + [(MEDIUM[0], 0, 2), (SMALL[3], B.HF_COPY_OWN, 2),
                                                                  (SMALL[3], 0, 1), (BASELINE[0], 0, 2), (SMALL[6], 0, 2)]
     for case, flags, mode in runs:
         print(f"[static {case['name']} flags {flags} multicast {mode}]", flush=True)
