@@ -128,8 +128,9 @@ def measured_ceilings(ar, n_dst, stream):
     """What this machine sustains for plain streams of known traffic, from the library's
     calibration kernels, in this process after the timed region: one-shot workgroups like the
     default kernel, a read-only, a write-only and a 1:1 stream, and the workload's own mix of
-    one read per n_dst writes (loaded once and stored n_dst times, or copied block-wise so
-    that L2 serves the re-reads).  The copies scribble over gen_buf."""
+    one read per n_dst writes (loaded once and stored n_dst times, copied block-wise so that
+    L2 serves the re-reads, or stored n_dst times after a load-only pass over the block).  The
+    copies scribble over gen_buf."""
     import torch
 
     from paper_2409_19256_amd import binding as B
@@ -149,8 +150,10 @@ def measured_ceilings(ar, n_dst, stream):
         torch.cuda.synchronize()
         return round(traffic / (a.elapsed_time(b) / reps * 1e-3) / 1e9, 1)
 
-    def fan(src, dst, n, blk, wg):
-        return lambda: B.check(B.hf_calib_fanout(src, dst, src_bytes, n, stride if n > 1 else src_bytes, blk, wg, stream), "hf_calib_fanout")
+    def fan(src, dst, n, blk, wg, method=None):
+        method = (B.HF_FANOUT_CACHE_BLOCKED if blk else B.HF_FANOUT_REGISTERS) if method is None else method
+        return lambda: B.check(B.hf_calib_fanout(src, dst, src_bytes, n, stride if n > 1 else src_bytes, method, blk, wg, stream),
+                               "hf_calib_fanout")
 
     t, g = ar.train_ptr, ar.gen_ptr
     out = {"unit": "GB/s", "source_bytes": src_bytes,
@@ -161,6 +164,8 @@ def measured_ceilings(ar, n_dst, stream):
         mix = {f"registers_{wg}B": timed(fan(t, g, n_dst, 0, wg), (1 + n_dst) * src_bytes) for wg in (1024, 4096)}
         mix.update({f"cache_blocked_{blk >> 20}MiB_{wg}B": timed(fan(t, g, n_dst, blk, wg), (1 + n_dst) * src_bytes)
                     for blk in (2 << 20, 4 << 20) for wg in (4096, 8192)})
+        mix.update({f"prefetched_{blk >> 20}MiB_1024B": timed(fan(t, g, n_dst, blk, 1024, B.HF_FANOUT_PREFETCHED), (1 + n_dst) * src_bytes)
+                    for blk in (8 << 20, 16 << 20)})
         out["mix"] = f"1 read : {n_dst} writes, destinations {stride} bytes apart"
         out["mix_variants"] = mix
         out["mix_best"] = max(mix.values())

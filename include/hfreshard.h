@@ -291,14 +291,19 @@ HF_API int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_str
  * dst_stride >= bytes, multiple of 256; nothing overlaps).  The traffic mix of a
  * transition in which every training piece is wanted by n_dst ranks, without any of its
  * geometry: the ceiling such a mix can reach on a box.
- * block_bytes == 0: every workgroup loads its part once and stores it n_dst times;
- * block_bytes > 0 (multiple of 64 KiB): a block of the source is copied to the first place,
- * then the same block to the second, ... (re-reads served by L2), like the library's
- * cache-blocked work list.  wg_bytes: bytes per workgroup, 1024 (one wavefront), 4096 or
- * 8192.  src == NULL: only the n_dst writes (of a constant pattern); dst == NULL: only the
- * read (block_bytes must then be 0).  Not part of the paper's method. */
-HF_API int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes,
-                    int wg_bytes, void *hip_stream);
+ * method HF_FANOUT_REGISTERS: every workgroup loads its part once and stores it n_dst times
+ *   (block_bytes ignored);
+ * HF_FANOUT_CACHE_BLOCKED: a block of block_bytes (multiple of 64 KiB) of the source is
+ *   copied to the first place, then the same block to the second, ... (re-reads served by
+ *   L2), like the library's cache-blocked work list;
+ * HF_FANOUT_PREFETCHED: a block is first loaded by workgroups that store nothing, then
+ *   loaded again (from L2) and stored n_dst times, like the library's prefetched list.
+ * wg_bytes: bytes per workgroup, 1024 (one wavefront), 4096 or 8192.  src == NULL: only the
+ * n_dst writes (of a constant pattern); dst == NULL: only the read (both: method
+ * HF_FANOUT_REGISTERS only).  Not part of the paper's method. */
+enum { HF_FANOUT_REGISTERS = 0, HF_FANOUT_CACHE_BLOCKED = 1, HF_FANOUT_PREFETCHED = 2 };
+HF_API int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, int method,
+                    size_t block_bytes, int wg_bytes, void *hip_stream);
 
 /* ---- tuning (host; takes effect on the next launch) -----------------------------
  * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES re-tile and re-upload; HF_PARAM_MULTICAST

@@ -39,6 +39,7 @@ HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
 HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS, HF_PARAM_OFFLOAD_WGS, HF_PARAM_ROW_INTERLEAVE, HF_PARAM_PREFETCH_BLOCK_BYTES = 8, 9, 10, 11, 12
 HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED, HF_MULTICAST_PREFETCHED = 0, 1, 2, 3
 HF_STATIC_SCRATCH_BYTES = 16 << 20
+HF_FANOUT_REGISTERS, HF_FANOUT_CACHE_BLOCKED, HF_FANOUT_PREFETCHED = 0, 1, 2
 HF_VARIANT_PERSISTENT, HF_VARIANT_ONE_WG_PER_TILE, HF_VARIANT_LDS_STAGED, HF_VARIANT_WAVE_PERSISTENT, HF_VARIANT_PARTS = 0, 1, 2, 3, 4
 
 TENSOR_NAMES = {
@@ -119,7 +120,7 @@ SIGNATURES = {
     "hf_gather_responses": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hf_plan_micro_dp_peer": (C.c_int, [_P, C.c_int, C.c_int]),
     "hf_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
-    "hf_calib_fanout": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p]),
+    "hf_calib_fanout": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_size_t, C.c_int, C.c_size_t, C.c_int, C.c_void_p]),
     "hf_offload_remote": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hf_reload_remote": (C.c_int, [_P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hf_plan_remote_bytes": (C.c_size_t, [_P]),

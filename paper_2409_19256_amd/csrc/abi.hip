@@ -651,10 +651,12 @@ int hf_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
   return HF_OK;
 }
 
-int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes, int wg_bytes,
-                    void *hip_stream) {
+int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, int method, size_t block_bytes,
+                    int wg_bytes, void *hip_stream) {
   if (!src && !dst) return fail(HF_EINVAL, "null buffers");
-  if ((!src || !dst) && block_bytes) return fail(HF_EINVAL, "fan-out copy: blocks need both a source and destinations");
+  if (method < HF_FANOUT_REGISTERS || method > HF_FANOUT_PREFETCHED) return fail(HF_EINVAL, "unknown fan-out method");
+  if ((!src || !dst) && method != HF_FANOUT_REGISTERS) return fail(HF_EINVAL, "fan-out copy: blocks need both a source and destinations");
+  if (method != HF_FANOUT_REGISTERS && block_bytes == 0) return fail(HF_EINVAL, "fan-out copy: this method needs a block size");
   if (n_dst < 1 || n_dst > 8) return fail(HF_EINVAL, "n_dst must be in [1, 8]");
   if (wg_bytes != 1024 && wg_bytes != 4096 && wg_bytes != 8192) return fail(HF_EINVAL, "wg_bytes must be 1024, 4096 or 8192");
   if (bytes == 0 || bytes % 8192 || dst_stride % 256 || dst_stride < bytes || block_bytes % 65536 ||
@@ -663,7 +665,7 @@ int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t 
   const char *s0 = static_cast<const char *>(src), *d0 = static_cast<const char *>(dst);
   const size_t span = (size_t)(n_dst - 1) * dst_stride + bytes;
   if (s0 && d0 && s0 < d0 + span && d0 < s0 + bytes) return fail(HF_EINVAL, "fan-out copy: buffers overlap");
-  const int e = hf::launch_calib_fanout(src, dst, bytes, n_dst, dst_stride, block_bytes, wg_bytes, hip_stream);
+  const int e = hf::launch_calib_fanout(src, dst, bytes, n_dst, dst_stride, method, block_bytes, wg_bytes, hip_stream);
   if (e == (int)hipErrorInvalidValue) return fail(HF_ERANGE, "fan-out copy: too many workgroups for one launch");
   if (e != 0) return fail(HF_EHIP, std::string("kernel launch: ") + hipGetErrorString(static_cast<hipError_t>(e)));
   return HF_OK;

@@ -270,11 +270,11 @@ int main(int argc, char **argv) {
     report("hipMemcpyAsync device to device", 2.0 * S, tm / 5);
     for (int w : {1024, 4096, 8192}) { // one short-lived workgroup per w bytes, like the library's default kernel
       char what[96];
-      if (time_calls(st, 2, 5, [&]() { return hf_calib_fanout(train, nullptr, S, 1, S, 0, w, st); }, &t)) return 1;
+      if (time_calls(st, 2, 5, [&]() { return hf_calib_fanout(train, nullptr, S, 1, S, HF_FANOUT_REGISTERS, 0, w, st); }, &t)) return 1;
       std::snprintf(what, sizeof what, "read only, %d B per workgroup", w);
       report(what, (double)S, t);
       for (int n_dst : {1, 3, 4}) {
-        if (time_calls(st, 2, 5, [&]() { return hf_calib_fanout(nullptr, gen, S, n_dst, S, 0, w, st); }, &t)) return 1;
+        if (time_calls(st, 2, 5, [&]() { return hf_calib_fanout(nullptr, gen, S, n_dst, S, HF_FANOUT_REGISTERS, 0, w, st); }, &t)) return 1;
         std::snprintf(what, sizeof what, "write only, %d streams, %d B per workgroup", n_dst, w);
         report(what, (double)n_dst * S, t);
       }
@@ -286,15 +286,20 @@ int main(int argc, char **argv) {
       for (size_t stride : strides) {
         if ((size_t)(n_dst - 1) * stride + S > gb) continue;
         for (int w : wgb) {
-          for (size_t block : {(size_t)0, (size_t)1 << 20, (size_t)2 << 20, (size_t)4 << 20}) {
-            if (n_dst == 1 && block) continue;
+          struct { int method; size_t block; const char *name; } forms[] = {
+              {HF_FANOUT_REGISTERS, 0, "registers"},
+              {HF_FANOUT_CACHE_BLOCKED, (size_t)1 << 20, "cache-blocked 1 MiB"},
+              {HF_FANOUT_CACHE_BLOCKED, (size_t)2 << 20, "cache-blocked 2 MiB"},
+              {HF_FANOUT_CACHE_BLOCKED, (size_t)4 << 20, "cache-blocked 4 MiB"},
+              {HF_FANOUT_PREFETCHED, (size_t)4 << 20, "prefetched 4 MiB"},
+              {HF_FANOUT_PREFETCHED, (size_t)8 << 20, "prefetched 8 MiB"},
+              {HF_FANOUT_PREFETCHED, (size_t)16 << 20, "prefetched 16 MiB"}};
+          for (const auto &f : forms) {
+            if (n_dst == 1 && f.method != HF_FANOUT_REGISTERS) continue;
             char what[160];
-            std::snprintf(what, sizeof what, "fan-out 1 read : %d writes, %s, %d B per workgroup, stride %zu", n_dst,
-                          block ? (block == (1u << 20) ? "cache-blocked 1 MiB" : block == (2u << 20) ? "cache-blocked 2 MiB" : "cache-blocked 4 MiB")
-                                : "registers",
-                          w, stride);
+            std::snprintf(what, sizeof what, "fan-out 1 read : %d writes, %s, %d B per workgroup, stride %zu", n_dst, f.name, w, stride);
             int rc = time_calls(st, 1, 4, [&]() {
-              const int r = hf_calib_fanout(train, gen, S, n_dst, stride, block, w, st);
+              const int r = hf_calib_fanout(train, gen, S, n_dst, stride, f.method, f.block, w, st);
               if (r) std::fprintf(stderr, "hf_calib_fanout: %s\n", hf_last_error());
               return r;
             }, &t);

@@ -27,7 +27,7 @@ int launch_tiles(const hf_tile *d_tiles, size_t n_tiles, const uint64_t *extra_d
 int launch_gather_slots(const int32_t *d_peers, uint32_t n_pairs, const void *in, void *out, size_t slot_bytes,
                         void *stream);
 // One read, n_dst writes of known traffic (see hf_calib_fanout).  Returns a hipError_t value.
-int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes,
+int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, int method, size_t block_bytes,
                         int wg_bytes, void *stream);
 // Plain grid-stride 16-byte copy (calibration); src == null: write only, dst == null: read only.
 int launch_calib_copy(const void *src, void *dst, size_t bytes, void *stream);

@@ -275,22 +275,24 @@ __global__ __launch_bounds__(kWG) void calib_write(u32x4 *__restrict__ dst, size
 }
 
 // One read, n_dst writes (hf_calib_fanout); src == null: writes only, dst == null: the
-// read only.  Workgroup b of a block pass copies
-// kUnroll vectors per lane; block_vecs == 0: every workgroup stores its vectors to all
-// n_dst places; otherwise the grid is (blocks x n_dst passes x workgroups per block) and
-// a workgroup stores to the place of its pass, so that passes 2.. re-read what pass 1
-// brought into L2.
+// read only.  A workgroup handles kUnroll vectors per lane.  method 0 (registers): every
+// workgroup stores its vectors to all n_dst places.  method 1 (cache-blocked): the grid is
+// (blocks x n_dst passes x workgroups per block) and a workgroup stores to the place of its
+// pass, so that passes 2.. re-read what pass 1 brought into L2.  method 2 (prefetched): the
+// grid is (blocks x 2 passes x workgroups per block); pass 0 only loads the block, pass 1
+// loads it again (from L2) and stores it to all n_dst places.
 template <int kThreads, int kUnroll>
 __global__ __launch_bounds__(kThreads) void calib_fanout(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n_vec,
-                                                         uint32_t n_dst, size_t stride_vec, uint32_t block_vecs) {
+                                                         uint32_t n_dst, size_t stride_vec, uint32_t block_vecs, int method) {
   constexpr uint32_t per_wg = kThreads * kUnroll;
   size_t first;
   uint32_t pass = 0;
-  if (block_vecs == 0) {
+  if (method == 0) {
     first = (size_t)blockIdx.x * per_wg;
   } else {
     const uint32_t wpb = block_vecs / per_wg; // workgroups per block pass
-    const uint32_t block = blockIdx.x / (wpb * n_dst), rest = blockIdx.x - block * (wpb * n_dst);
+    const uint32_t passes = method == 1 ? n_dst : 2;
+    const uint32_t block = blockIdx.x / (wpb * passes), rest = blockIdx.x - block * (wpb * passes);
     pass = rest / wpb;
     first = (size_t)block * block_vecs + (size_t)(rest - pass * wpb) * per_wg;
   }
@@ -299,27 +301,20 @@ __global__ __launch_bounds__(kThreads) void calib_fanout(const u32x4 *__restrict
   for (int k = 0; k < kUnroll; ++k) {
     const size_t i = first + (size_t)k * kThreads + threadIdx.x;
     v[k] = u32x4{0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au, 0x5A5A5A5Au};
-    if (src && i < n_vec) v[k] = block_vecs ? src[i] : __builtin_nontemporal_load(src + i);
+    if (src && i < n_vec) v[k] = method ? src[i] : __builtin_nontemporal_load(src + i);
   }
-  if (!dst) { // read only
+  if (!dst || (method == 2 && pass == 0)) { // read only
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k) keep_alive(v[k]);
     return;
   }
-  if (block_vecs == 0) {
-    for (uint32_t j = 0; j < n_dst; ++j)
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const size_t i = first + (size_t)k * kThreads + threadIdx.x;
-        if (i < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)j * stride_vec + i);
-      }
-  } else {
+  const uint32_t j0 = method == 1 ? pass : 0, j1 = method == 1 ? pass + 1 : n_dst;
+  for (uint32_t j = j0; j < j1; ++j)
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k) {
       const size_t i = first + (size_t)k * kThreads + threadIdx.x;
-      if (i < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)pass * stride_vec + i);
+      if (i < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)j * stride_vec + i);
     }
-  }
 }
 
 template <int kPolicy, int kList>
@@ -426,15 +421,15 @@ int launch_gather_slots(const int32_t *d_peers, uint32_t n_pairs, const void *in
   return (int)hipGetLastError();
 }
 
-int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, size_t block_bytes,
+int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, size_t dst_stride, int method, size_t block_bytes,
                         int wg_bytes, void *stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t n_vec = bytes / 16, stride_vec = dst_stride / 16;
   const size_t wgs_one_pass = (bytes + wg_bytes - 1) / wg_bytes;
   size_t grid = wgs_one_pass;
-  if (block_bytes) {
+  if (method) {
     const size_t blocks = (bytes + block_bytes - 1) / block_bytes;
-    grid = blocks * (size_t)n_dst * (block_bytes / wg_bytes);
+    grid = blocks * (size_t)(method == 1 ? n_dst : 2) * (block_bytes / wg_bytes);
   }
   const int threads = wg_bytes == 1024 ? kWave : kWG;
   if (grid == 0 || grid > 0xFFFFFFFFull / threads) return (int)hipErrorInvalidValue; // beyond one HIP grid
@@ -442,9 +437,9 @@ int launch_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, siz
   const u32x4 *s = static_cast<const u32x4 *>(src);
   u32x4 *d = static_cast<u32x4 *>(dst);
   const uint32_t bv = (uint32_t)(block_bytes / 16);
-  if (wg_bytes == 1024) hipLaunchKernelGGL((calib_fanout<kWave, 1>), g, dim3(kWave), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
-  else if (wg_bytes == 4096) hipLaunchKernelGGL((calib_fanout<kWG, 1>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
-  else hipLaunchKernelGGL((calib_fanout<kWG, 2>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv);
+  if (wg_bytes == 1024) hipLaunchKernelGGL((calib_fanout<kWave, 1>), g, dim3(kWave), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv, method);
+  else if (wg_bytes == 4096) hipLaunchKernelGGL((calib_fanout<kWG, 1>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv, method);
+  else hipLaunchKernelGGL((calib_fanout<kWG, 2>), g, dim3(kWG), 0, st, s, d, n_vec, (uint32_t)n_dst, stride_vec, bv, method);
   return (int)hipGetLastError();
 }
 

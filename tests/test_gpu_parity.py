@@ -608,17 +608,19 @@ def test_fanout_calibration_kernels_copy_exactly():
     n = 3 * 65536 + 8192                                   # bytes: several blocks and a ragged one
     src = torch.randint(-30000, 30000, (n // 2,), dtype=torch.int16, device="cuda")
     st = Arena.stream_handle()
-    for block, wg in [(0, 1024), (0, 4096), (0, 8192), (65536, 1024), (65536, 4096), (131072, 8192)]:
+    R, CB, PF = B.HF_FANOUT_REGISTERS, B.HF_FANOUT_CACHE_BLOCKED, B.HF_FANOUT_PREFETCHED
+    for method, block, wg in [(R, 0, 1024), (R, 0, 4096), (R, 0, 8192), (CB, 65536, 1024), (CB, 65536, 4096), (CB, 131072, 8192),
+                              (PF, 65536, 1024), (PF, 131072, 4096), (PF, 65536, 8192)]:
         for n_dst in (1, 3):
             stride = n + 256
             dst = torch.full((n_dst * stride // 2,), 77, dtype=torch.int16, device="cuda")
-            B.check(B.hf_calib_fanout(src.data_ptr(), dst.data_ptr(), n, n_dst, stride, block, wg, st), "fanout")
+            B.check(B.hf_calib_fanout(src.data_ptr(), dst.data_ptr(), n, n_dst, stride, method, block, wg, st), "fanout")
             torch.cuda.synchronize()
             for j in range(n_dst):
-                assert torch.equal(dst[j * stride // 2: j * stride // 2 + n // 2], src), (block, wg, n_dst, j)
+                assert torch.equal(dst[j * stride // 2: j * stride // 2 + n // 2], src), (method, block, wg, n_dst, j)
                 assert bool((dst[j * stride // 2 + n // 2: (j + 1) * stride // 2] == 77).all())
     dst = torch.full((n // 2,), 77, dtype=torch.int16, device="cuda")
-    B.check(B.hf_calib_fanout(None, dst.data_ptr(), n, 1, n, 0, 4096, st), "write only")
-    B.check(B.hf_calib_fanout(src.data_ptr(), None, n, 1, n, 0, 4096, st), "read only")
+    B.check(B.hf_calib_fanout(None, dst.data_ptr(), n, 1, n, R, 0, 4096, st), "write only")
+    B.check(B.hf_calib_fanout(src.data_ptr(), None, n, 1, n, R, 0, 4096, st), "read only")
     torch.cuda.synchronize()
     assert bool((dst == 0x5A5A).all())

@@ -537,12 +537,14 @@ def test_error_codes():
         assert B.hf_calib_copy(None, None, 16, None) == B.HF_EINVAL
         assert B.hf_calib_copy(256, 4096, 24, None) == B.HF_EINVAL
         assert B.hf_calib_copy(256, 512, 1024, None) == B.HF_EINVAL      # overlap
-        assert B.hf_calib_fanout(None, None, 8192, 1, 8192, 0, 4096, None) == B.HF_EINVAL
-        assert B.hf_calib_fanout(256, 1 << 20, 8192, 9, 8192, 0, 4096, None) == B.HF_EINVAL     # n_dst
-        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 4096, 0, 4096, None) == B.HF_EINVAL     # stride < bytes
-        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 8192, 0, 2048, None) == B.HF_EINVAL     # wg_bytes
-        assert B.hf_calib_fanout(256, 4096, 8192, 1, 8192, 0, 4096, None) == B.HF_EINVAL        # overlap
-        assert B.hf_calib_fanout(256, None, 8192, 1, 8192, 65536, 4096, None) == B.HF_EINVAL    # blocks need both
+        assert B.hf_calib_fanout(None, None, 8192, 1, 8192, 0, 0, 4096, None) == B.HF_EINVAL
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 9, 8192, 0, 0, 4096, None) == B.HF_EINVAL     # n_dst
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 4096, 0, 0, 4096, None) == B.HF_EINVAL     # stride < bytes
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 8192, 0, 0, 2048, None) == B.HF_EINVAL     # wg_bytes
+        assert B.hf_calib_fanout(256, 4096, 8192, 1, 8192, 0, 0, 4096, None) == B.HF_EINVAL        # overlap
+        assert B.hf_calib_fanout(256, None, 8192, 1, 8192, 1, 65536, 4096, None) == B.HF_EINVAL    # blocks need both
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 8192, 2, 0, 4096, None) == B.HF_EINVAL     # method without a block size
+        assert B.hf_calib_fanout(256, 1 << 20, 8192, 3, 8192, 3, 65536, 4096, None) == B.HF_EINVAL # unknown method
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_OFFLOAD_WGS, 0)
         d = B.hf_desc()
