@@ -276,7 +276,8 @@ HF_API size_t hf_plan_remote_rank_offset(const hf_plan *plan, int rank); /* (siz
  * the hot path): HF_EINVAL if a pointer is null or not 256-byte aligned, if the ranges
  * overlap, or if train_len / gen_len (bytes the caller owns from the pointers on) are
  * smaller than hf_plan_train_bytes / hf_plan_gen_bytes.  With a device plan the ranges
- * must also lie inside device allocations of the HIP runtime (HF_ERANGE otherwise). */
+ * must also lie inside device allocations of the HIP runtime (HF_ERANGE otherwise).
+ * train_buf may be null (train_len is then ignored) for a HF_GATHER_FROM_GEN plan. */
 HF_API int hf_plan_check_buffers(const hf_plan *plan, const void *train_buf, size_t train_len, const void *gen_buf,
                           size_t gen_len);
 

@@ -344,17 +344,17 @@ size_t hf_plan_remote_rank_offset(const hf_plan *plan, int rank) {
 }
 
 int hf_plan_check_buffers(const hf_plan *plan, const void *train_buf, size_t train_len, const void *gen_buf, size_t gen_len) {
-  if (!plan || !train_buf || !gen_buf) return fail(HF_EINVAL, "null plan or buffer");
+  if (!plan) return fail(HF_EINVAL, "null plan or buffer");
   const hf::Plan &p = plan->p;
-  if ((reinterpret_cast<uintptr_t>(train_buf) | reinterpret_cast<uintptr_t>(gen_buf)) % 256)
-    return fail(HF_EINVAL, "train_buf and gen_buf must be 256-byte aligned");
-  if (train_len < p.train_bytes) return fail(HF_EINVAL, "train_buf is shorter than hf_plan_train_bytes");
+  // a plan that gathers out of the generation buffers never touches train_buf
+  if (int rc = check_buffers(p, train_buf, gen_buf, (p.flags & HF_GATHER_FROM_GEN) != 0)) return rc;
+  if (train_buf && train_len < p.train_bytes) return fail(HF_EINVAL, "train_buf is shorter than hf_plan_train_bytes");
   if (gen_len < p.gen_bytes) return fail(HF_EINVAL, "gen_buf is shorter than hf_plan_gen_bytes");
-  const char *t0 = static_cast<const char *>(train_buf), *g0 = static_cast<const char *>(gen_buf);
-  if (t0 < g0 + p.gen_bytes && g0 < t0 + p.train_bytes) return fail(HF_EINVAL, "train_buf and gen_buf overlap");
   if (p.flags & HF_PLAN_HOST_ONLY) return HF_OK;
-  struct { const char *ptr; size_t need; const char *name; } bufs[] = {{t0, p.train_bytes, "train_buf"}, {g0, p.gen_bytes, "gen_buf"}};
+  struct { const char *ptr; size_t need; const char *name; } bufs[] = {{static_cast<const char *>(train_buf), p.train_bytes, "train_buf"},
+                                                                        {static_cast<const char *>(gen_buf), p.gen_bytes, "gen_buf"}};
   for (auto &b : bufs) {
+    if (!b.ptr) continue;
     void *base = nullptr;
     size_t size = 0;
     if (hipMemGetAddressRange(reinterpret_cast<hipDeviceptr_t *>(&base), &size, const_cast<char *>(b.ptr)) != hipSuccess || !base) {

@@ -472,6 +472,10 @@ def test_check_buffers_on_the_host():
         assert B.hf_plan_check_buffers(pl._h, base + 2, tb, base + (1 << 24), gb) == B.HF_EINVAL
         assert B.hf_plan_check_buffers(pl._h, base, tb, base + 256, gb) == B.HF_EINVAL       # overlap
         assert B.hf_plan_check_buffers(pl._h, None, tb, base, gb) == B.HF_EINVAL
+    with make_plan(SMALL[0], HOST | B.HF_GATHER_FROM_GEN) as pl:     # never reads train_buf: it may be absent
+        assert B.hf_plan_check_buffers(pl._h, None, 0, 1 << 20, pl.gen_bytes) == B.HF_OK
+        assert B.hf_plan_check_buffers(pl._h, None, 0, 1 << 20, pl.gen_bytes - 2) == B.HF_EINVAL
+        assert B.hf_plan_check_buffers(pl._h, 1 << 20, pl.train_bytes, 1 << 20, pl.gen_bytes) == B.HF_EINVAL   # overlap
 
 
 def test_kind_restriction_is_a_debug_entry_and_makes_the_plan_invalid():
