@@ -317,8 +317,11 @@ enum {
   HF_PARAM_MULTICAST = 3,    /* HF_MULTICAST_*: how train->gen serves a training piece that
                                 several ranks of a micro-DP group want.  Same result in
                                 every mode; the modes differ in HBM reads and in speed.
-                                Default: HF_MULTICAST_CACHE_BLOCKED, and
-                                HF_MULTICAST_PREFETCHED for HF_COPY_OWN plans.  When no piece
+                                Default (and HF_MULTICAST_AUTO): chosen from the fan-out of
+                                the list, i.e. bytes written per distinct byte read, as
+                                measured: about 2 -> REGISTERS, 3 -> CACHE_BLOCKED, 4 and
+                                more -> PREFETCHED (re-chosen when the list is rebuilt;
+                                hf_plan_get_param returns the mode in force).  When no piece
                                 of the plan has more than one destination (e.g. only one
                                 rank per micro-DP group is materialised) every mode runs
                                 as HF_MULTICAST_OFF, and hf_plan_get_param says so.      */
@@ -360,6 +363,7 @@ enum {
                                 every other kernel's memory traffic by orders of magnitude */
 };
 enum {
+  HF_MULTICAST_AUTO = -1,     /* hf_plan_set_param only: back to the library's choice     */
   HF_MULTICAST_OFF = 0,       /* one read per destination, destination-major order        */
   HF_MULTICAST_REGISTERS = 1, /* a workgroup loads a tile once and stores it to every
                                  destination                                             */

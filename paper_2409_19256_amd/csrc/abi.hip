@@ -417,8 +417,9 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     p.variant = value;
     return HF_OK;
   case HF_PARAM_MULTICAST:
-    if (value < HF_MULTICAST_OFF || value > HF_MULTICAST_PREFETCHED) return fail(HF_EINVAL, "unknown multicast mode");
-    p.multicast = value;
+    if (value < HF_MULTICAST_AUTO || value > HF_MULTICAST_PREFETCHED) return fail(HF_EINVAL, "unknown multicast mode");
+    p.multicast_auto = value == HF_MULTICAST_AUTO;
+    p.multicast = p.multicast_auto ? hf::default_multicast(p) : value;
     p.serial = g_next_serial++;
     if (!(p.flags & HF_PLAN_HOST_ONLY)) return upload_forward_lists(p);
     return HF_OK;

@@ -91,7 +91,17 @@ int main(int argc, char **argv) {
   long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0,
             wg_threads = 0, resp_tokens = 0, ceilings = 0, offload_wgs = 0, row_interleave = -1, pf_block = 0;
   unsigned flags = HF_SKIP_OWN;
-  std::vector<int32_t> mat_override;
+  std::vector<int32_t> mat_override, train_override, gen_override;
+  auto int_list = [](const std::string &list) {
+    std::vector<int32_t> out;
+    for (size_t p0 = 0; p0 < list.size();) {
+      size_t p1 = list.find(',', p0);
+      if (p1 == std::string::npos) p1 = list.size();
+      out.push_back(std::atoi(list.substr(p0, p1 - p0).c_str()));
+      p0 = p1 + 1;
+    }
+    return out;
+  };
   for (int i = 1; i < argc; ++i) {
     const std::string a = argv[i];
     auto val = [&]() -> long long { return i + 1 < argc ? std::atoll(argv[++i]) : 0; };
@@ -120,24 +130,32 @@ int main(int argc, char **argv) {
     else if (a == "--offload-wgs") offload_wgs = val();
     else if (a == "--row-interleave") row_interleave = val();
     else if (a == "--prefetch-block-bytes") pf_block = val();
-    else if (a == "--mat") { // comma-separated ranks to materialise instead of the configuration's
-      const std::string list = i + 1 < argc ? argv[++i] : "";
-      for (size_t p0 = 0; p0 < list.size();) {
-        size_t p1 = list.find(',', p0);
-        if (p1 == std::string::npos) p1 = list.size();
-        mat_override.push_back(std::atoi(list.substr(p0, p1 - p0).c_str()));
-        p0 = p1 + 1;
-      }
-    } else {
+    else if (a == "--mat") mat_override = int_list(i + 1 < argc ? argv[++i] : "");     // ranks to materialise instead of the configuration's
+    else if (a == "--train") train_override = int_list(i + 1 < argc ? argv[++i] : ""); // p,t,d instead of the configuration's
+    else if (a == "--gen") gen_override = int_list(i + 1 < argc ? argv[++i] : "");     // p_g,t_g instead of the configuration's
+    else {
       std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back | --install-own] [--copy-own] [--vanilla] [--from-gen] "
                            "[--multicast 0|1|2|3] [--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] "
-                           "[--cache-policy P] [--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--mat r0,r1,..] "
+                           "[--cache-policy P] [--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--mat r0,r1,..] [--train p,t,d] [--gen pg,tg] "
                            "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]] [--row-interleave 0|1] [--prefetch-block-bytes B]\n");
       return 2;
     }
   }
   if (config < 1 || config > 5 || steps < 1 || warmup < 0) { std::fprintf(stderr, "bad arguments\n"); return 2; }
-  const Config &c = configs[config - 1];
+  if ((!train_override.empty() && train_override.size() != 3) || (!gen_override.empty() && gen_override.size() != 2)) {
+    std::fprintf(stderr, "--train takes p,t,d and --gen takes pg,tg\n");
+    return 2;
+  }
+  Config c = configs[config - 1];
+  std::string name = c.name;
+  if (!train_override.empty() || !gen_override.empty()) {
+    if (!train_override.empty()) c.t = hf_train_layout{train_override[0], train_override[1], train_override[2]};
+    if (!gen_override.empty()) { c.pg = gen_override[0]; c.tg = gen_override[1]; }
+    c.mat.clear(); // the configuration's subset belongs to its own layout
+    name = name.substr(0, name.find('_')) + "_p" + std::to_string(c.t.pp) + "t" + std::to_string(c.t.tp) + "d" + std::to_string(c.t.dp) +
+           "_to_p" + std::to_string(c.pg) + "t" + std::to_string(c.tg);
+    c.name = name.c_str();
+  }
   const std::vector<int32_t> &mat = mat_override.empty() ? c.mat : mat_override;
   hf_gen_layout gl{c.pg, c.tg, flags, mat.empty() ? nullptr : mat.data(), (int32_t)mat.size()};
   hf_plan *plan = nullptr;

@@ -95,6 +95,7 @@ struct Plan {
   int64_t grid_wgs = 2048;
   int64_t variant = HF_VARIANT_PARTS;
   int64_t multicast = HF_MULTICAST_CACHE_BLOCKED;
+  bool multicast_auto = true; // the mode follows the list's fan-out until the caller names one
   int64_t mc_block_bytes = 2 << 20;
   int64_t prefetch_block_bytes = 8 << 20;
   int64_t cache_policy = -1; // auto
@@ -134,6 +135,7 @@ struct Plan {
 int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_layout &gl, Plan &out, std::string &err);
 // (Re)creates the tile lists from the descriptors with out.tile_bytes.
 int build_tiles(Plan &pl, std::string &err);
+int64_t default_multicast(const Plan &pl); // needs the byte totals build_tiles sets
 // Host-side consistency check (see hf_plan_validate).
 int validate_plan(const Plan &pl, std::string &err);
 uint64_t desc_bytes(const hf_desc &d);

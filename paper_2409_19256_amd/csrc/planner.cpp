@@ -184,10 +184,7 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
   pl.m = m;
   pl.p = tl.pp; pl.t = tl.tp; pl.d = tl.dp; pl.pg = gl.pp; pl.tg = gl.tp;
   pl.flags = gl.flags;
-  // measured default: with the own pieces in the list (four and more destinations per piece on
-  // the benchmark shapes) the prefetched order beats the cache-blocked one by 3-6 %; without
-  // them the cache-blocked order is level with or ahead of the others
-  pl.multicast = (gl.flags & HF_COPY_OWN) ? HF_MULTICAST_PREFETCHED : HF_MULTICAST_CACHE_BLOCKED;
+  pl.multicast_auto = true; // build_tiles picks the mode from the fan-out of the list
   pl.a = pl.t / pl.tg;
   pl.b = pl.p / pl.pg;
   pl.dg = pl.a * pl.b;
@@ -454,6 +451,21 @@ void tile_desc(std::vector<hf_tile> &out, const hf_desc &d, uint64_t tile_bytes)
 
 } // namespace
 
+// Multicast mode when the caller leaves the choice to the library, from the list's fan-out
+// (bytes written per distinct byte read).  Measured on the Llama-7B and 13B shapes under
+// training TP 8 with generation TP 1, 2, 4, own pieces in the list or not, in several
+// processes on several machines:
+//   2 destinations per piece: registers 3-5 % ahead of cache-blocked, prefetched 15 % behind;
+//   3: cache-blocked and registers level on average, registers varying by 10 % from process
+//      to process, prefetched 4 % behind;
+//   4: prefetched level with or ahead of the others and the steadiest;
+//   7 and 8: prefetched and registers level, cache-blocked 10-13 % behind.
+int64_t default_multicast(const Plan &pl) {
+  if (!pl.unique_bytes[0]) return HF_MULTICAST_CACHE_BLOCKED;
+  const double fan = (double)pl.moved_bytes[0] / (double)pl.unique_bytes[0];
+  return fan < 2.5 ? HF_MULTICAST_REGISTERS : fan < 3.5 ? HF_MULTICAST_CACHE_BLOCKED : HF_MULTICAST_PREFETCHED;
+}
+
 int build_tiles(Plan &pl, std::string &err) {
   if (pl.tile_bytes < 4096 || pl.tile_bytes > (4 << 20) || pl.tile_bytes % 4096) {
     err = "tile bytes must be a multiple of 4096 in [4096, 4 MiB]";
@@ -651,6 +663,7 @@ int build_tiles(Plan &pl, std::string &err) {
     }
     flush();
   }
+  if (pl.multicast_auto) pl.multicast = default_multicast(pl);
   if (pl.tiles_fwd.size() >= (1ull << 31) || pl.tiles_back.size() >= (1ull << 31)) {
     err = "too many tiles; raise the tile size";
     return HF_ERANGE;

@@ -18,6 +18,7 @@ import torch
 from paper_2409_19256_amd import binding as B
 from paper_2409_19256_amd.arena import Arena
 from seeded_inputs import config_seed, fill_regions_torch, tensor_uid
+from oracle.reshard_oracle import GenLayout
 from tests.cases import BASELINE, MEDIUM, SMALL
 from tests.libcases import make_plan
 from tests.oracle_util import POISON, make_oracle, mat_ranks, seeded_train_buf, source_index_map
@@ -554,6 +555,16 @@ def test_llama34b_gqa_full_size():
 
 def test_llama70b_gqa_full_size():
     _check_full_size_streaming(BASELINE[4], 4)
+
+
+@pytest.mark.parametrize("t_g", [1, 4])
+def test_llama7b_generation_tp_sweep(t_g):
+    """Section 8.4 ("Transition and generation time") varies the generation TP size of the 7B
+    actor under training layout 1-8-d: t_g = 1 (micro-DP 8: every piece goes to seven peers),
+    2 (the headline configuration above), 4 (micro-DP 2: one peer), 8 (nothing to move).
+    Full size, default launch configuration, every tensor of every rank against the oracle."""
+    case = dict(BASELINE[1], name=f"llama7b_tp8_to_tp{t_g}", gen=GenLayout(1, t_g))
+    _check_full_size_streaming(case, 1)
 
 
 def test_refresh_after_the_training_shards_change():

@@ -461,6 +461,32 @@ def test_gather_from_gen_needs_the_whole_micro_dp_group_and_the_hybridflow_group
     assert code(G, mat=[0, 1], train=(2, 4, 1), gen=(1, 2)) == B.HF_EINVAL
 
 
+def test_default_multicast_mode_follows_the_fan_out():
+    """Bytes written per distinct byte read: about 2 -> registers, 3 -> cache-blocked, 4 and more -> prefetched;
+    a caller's choice sticks until HF_MULTICAST_AUTO hands it back."""
+    from oracle.reshard_oracle import GenLayout, Model, TrainLayout
+    m = Model(2, 64, 8, 8, 8, 96, 128)
+    want = {(4, 0): B.HF_MULTICAST_OFF, (4, B.HF_COPY_OWN): B.HF_MULTICAST_REGISTERS,                 # 1 and 2 destinations
+            (2, 0): B.HF_MULTICAST_CACHE_BLOCKED, (2, B.HF_COPY_OWN): B.HF_MULTICAST_PREFETCHED,      # 3 and 4
+            (1, 0): B.HF_MULTICAST_PREFETCHED, (1, B.HF_COPY_OWN): B.HF_MULTICAST_PREFETCHED}         # 7 and 8
+    for (tg, flag), mode in want.items():
+        case = dict(name="fan", model=m, train=TrainLayout(1, 8, 1), gen=GenLayout(1, tg))
+        with make_plan(case, HOST | flag) as pl:
+            fan = pl.bytes_moved(0) / pl.unique_src_bytes(0)
+            assert round(fan) == 8 // tg - (0 if flag else 1)
+            assert pl.get_param(B.HF_PARAM_MULTICAST) == mode, (tg, flag)
+            if mode != B.HF_MULTICAST_OFF:
+                other = B.HF_MULTICAST_REGISTERS if mode != B.HF_MULTICAST_REGISTERS else B.HF_MULTICAST_CACHE_BLOCKED
+                pl.set_param(B.HF_PARAM_MULTICAST, other)
+                pl.set_param(B.HF_PARAM_TILE_BYTES, 8192)                 # a rebuild keeps the caller's choice
+                assert pl.get_param(B.HF_PARAM_MULTICAST) == other
+                pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_AUTO)
+                assert pl.get_param(B.HF_PARAM_MULTICAST) == mode
+            pl.validate()
+    with make_plan(SMALL[0], HOST) as pl:
+        assert B.hf_plan_set_param(pl._h, B.HF_PARAM_MULTICAST, -2) == B.HF_EINVAL
+
+
 def test_check_buffers_on_the_host():
     with make_plan(SMALL[0], HOST) as pl:
         tb, gb = pl.train_bytes, pl.gen_bytes
