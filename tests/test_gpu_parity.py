@@ -557,6 +557,19 @@ def test_llama70b_gqa_full_size():
     _check_full_size_streaming(BASELINE[4], 4)
 
 
+def test_llama34b_one_whole_micro_dp_group_full_size():
+    """Config 4's shape with the four ranks of ONE micro-DP group (two TP neighbours x two merged
+    stages) instead of four unrelated ranks: every piece then has three destinations on the GPU
+    and the multicast work list runs at the 34B GQA shape."""
+    _check_full_size_streaming(dict(BASELINE[3], name="llama34b_gqa_group_0_1_8_9", mat=[0, 1, 8, 9]), 3)
+
+
+def test_llama70b_two_members_of_one_micro_dp_group_full_size():
+    """Config 5's shape with two members of one micro-DP group: pieces of the other six members
+    have two destinations, the two members' own pieces one (mixed fan-out in one list)."""
+    _check_full_size_streaming(dict(BASELINE[4], name="llama70b_gqa_ranks_0_1", mat=[0, 1]), 4)
+
+
 @pytest.mark.parametrize("t_g", [1, 4])
 def test_llama7b_generation_tp_sweep(t_g):
     """Section 8.4 ("Transition and generation time") varies the generation TP size of the 7B
