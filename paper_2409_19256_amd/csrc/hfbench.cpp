@@ -300,7 +300,7 @@ int main(int argc, char **argv) {
     const size_t region = gb / std::max<size_t>(1, (size_t)hf_plan_num_mat(plan)); // distance of two ranks' generation buffers
     const size_t strides[] = {S, (S + (1u << 20)) / 256 * 256, std::max(S, region / 256 * 256)};
     const int wgb[] = {1024, 4096, 8192};
-    for (int n_dst : {1, 3, 4}) {
+    for (int n_dst : {1, 2, 3, 4, 7}) {
       for (size_t stride : strides) {
         if ((size_t)(n_dst - 1) * stride + S > gb) continue;
         for (int w : wgb) {
