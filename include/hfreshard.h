@@ -307,9 +307,9 @@ HF_API int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, 
                     size_t block_bytes, int wg_bytes, void *hip_stream);
 
 /* ---- tuning (host; takes effect on the next launch) -----------------------------
- * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES re-tile and re-upload; HF_PARAM_MULTICAST
- * uploads the work list of the new mode and frees the old one (they allocate; not for the
- * hot path).  Only the work lists of the current mode are resident on the device. */
+ * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_PREFETCH_BLOCK_BYTES and
+ * HF_PARAM_ROW_INTERLEAVE re-tile and re-upload; HF_PARAM_MULTICAST uploads the work list of
+ * the new mode and frees the old one (they allocate; not for the hot path).  Only the work lists of the current mode are resident on the device. */
 enum {
   HF_PARAM_TILE_BYTES = 0,   /* bytes of work per tile, 4096 .. 4 MiB, multiple of 4096   */
   HF_PARAM_GRID_WGS = 1,     /* workgroups of the persistent kernels, 1 .. 65536          */
@@ -326,8 +326,8 @@ enum {
                                 rank per micro-DP group is materialised) every mode runs
                                 as HF_MULTICAST_OFF, and hf_plan_get_param says so.      */
   HF_PARAM_CACHE_POLICY = 4, /* -1 (default): chosen by the library (0 for one-to-one
-                                streaming lists, 5 for the cache-blocked list, 4 for
-                                multi-destination tiles); 0 = non-temporal loads and
+                                streaming lists, 5 for the cache-blocked and the prefetched
+                                list, 4 for the register-multicast list); 0 = non-temporal loads and
                                 system-scope streaming stores; bit 0 = plain loads,
                                 bit 1 = plain stores, 4 / 5 = compiler non-temporal stores
                                 with non-temporal / plain loads (not for
@@ -336,7 +336,7 @@ enum {
                                 from 4096 to 32768 (1024 to 8192 with 64-lane workgroups;
                                 values outside the range are clamped), or 0 (default) =
                                 automatic: 8192 for the cache-blocked train->gen list,
-                                1024 for plain streaming lists                           */
+                                1024 for every other list                                */
   HF_PARAM_MC_BLOCK_BYTES = 6, /* HF_MULTICAST_CACHE_BLOCKED: source bytes per block,
                                 1 MiB .. 1 GiB, default 2 MiB (re-tiles and re-uploads)  */
   HF_PARAM_MAX_WGS_PER_LAUNCH = 8, /* HF_VARIANT_PARTS / ONE_WG_PER_TILE: a work list that needs
@@ -346,7 +346,7 @@ enum {
                                 fewer than 2^32 threads)                                  */
   HF_PARAM_WG_THREADS = 9,   /* HF_VARIANT_PARTS: lanes per workgroup: 256, 64, or 0 (default) =
                                 automatic: 256 for the cache-blocked train->gen list, 64
-                                (one wavefront) for plain streaming lists                */
+                                (one wavefront) for every other list                     */
   HF_PARAM_PREFETCH_BLOCK_BYTES = 12, /* HF_MULTICAST_PREFETCHED: source bytes per block, 1 MiB ..
                                 64 MiB, default 8 MiB: the eight 4 MiB L2s must hold a block
                                 until its copies are done (re-tiles and re-uploads)        */
