@@ -75,7 +75,26 @@ VARIANTS = [(B.HF_VARIANT_PERSISTENT, 128 * 1024, 2048, 1), (B.HF_VARIANT_PERSIS
             (B.HF_VARIANT_PARTS, 12288, 8192, 1), (B.HF_VARIANT_PARTS, 128 * 1024, 4096, 2),
             (B.HF_VARIANT_PERSISTENT, 64 * 1024, 1024, 2), (B.HF_VARIANT_PARTS, 64 * 1024, -2048, 2),
             (B.HF_VARIANT_PARTS, 16 * 1024, -1024, 1), (B.HF_VARIANT_PARTS, 128 * 1024, -1024, 3),
-            (B.HF_VARIANT_PERSISTENT, 32 * 1024, 64, 3), (B.HF_VARIANT_PARTS, 8192, 4096, 3)]
+            (B.HF_VARIANT_PERSISTENT, 32 * 1024, 64, 3), (B.HF_VARIANT_PARTS, 8192, 4096, 3),
+            (B.HF_VARIANT_PARTS, 128 * 1024, None, B.HF_MULTICAST_AUTO)]   # last: everything left to the library
+
+
+def _configure(pl, variant, tile_bytes, grid, multicast):
+    pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
+    if grid is None:
+        pass                                                      # launch shape chosen by the library
+    elif variant == B.HF_VARIANT_PARTS:
+        pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))            # third field = bytes per workgroup,
+        pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)   # negative: 64-lane workgroups
+    else:
+        pl.set_param(B.HF_PARAM_GRID_WGS, grid)
+    pl.set_param(B.HF_PARAM_VARIANT, variant)
+    pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)   # leave the automatic choice, then return to it or not
+    pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+    if multicast in (B.HF_MULTICAST_CACHE_BLOCKED, B.HF_MULTICAST_AUTO):
+        pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)           # several blocks even at these sizes
+    if multicast in (B.HF_MULTICAST_PREFETCHED, B.HF_MULTICAST_AUTO):
+        pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 1 << 20)
 
 
 @pytest.mark.parametrize("case", SMALL + [BASELINE[0]] + MEDIUM, ids=lambda c: c["name"])
@@ -92,18 +111,7 @@ def test_whole_buffers_match_oracle(case):
         _say(f"[case {case['name']} variant {variant} tile {tile_bytes} grid {grid} multicast {multicast}]")
         # --- COPY_OWN: complete generation buffers, padding untouched
         with make_plan(case, B.HF_COPY_OWN) as pl:
-            pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
-            if variant == B.HF_VARIANT_PARTS:
-                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))  # third field = bytes per workgroup,
-                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)  # negative: 64-lane workgroups
-            else:
-                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
-            pl.set_param(B.HF_PARAM_VARIANT, variant)
-            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
-            if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
-                pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
-            if multicast == B.HF_MULTICAST_PREFETCHED:
-                pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 1 << 20)
+            _configure(pl, variant, tile_bytes, grid, multicast)
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
             ar.gen.fill_(_i16(POISON))
@@ -113,18 +121,7 @@ def test_whole_buffers_match_oracle(case):
             assert np.array_equal(_d2h(ar.train), train)          # the source is never written
         # --- SKIP_OWN: only remote pieces written; install_own + execute = complete; reverse
         with make_plan(case, 0) as pl:
-            pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
-            if variant == B.HF_VARIANT_PARTS:
-                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))  # third field = bytes per workgroup,
-                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)  # negative: 64-lane workgroups
-            else:
-                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
-            pl.set_param(B.HF_PARAM_VARIANT, variant)
-            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
-            if multicast == B.HF_MULTICAST_CACHE_BLOCKED:
-                pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, 1 << 20)   # several blocks even at these sizes
-            if multicast == B.HF_MULTICAST_PREFETCHED:
-                pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 1 << 20)
+            _configure(pl, variant, tile_bytes, grid, multicast)
             assert pl.bytes_moved(0) == 2 * int(remote.sum())
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
@@ -160,17 +157,10 @@ def test_gather_out_of_the_generation_buffers(case):
     start[own] = complete[own]
     want = orc.gather_in_place(start.copy(), ranks)
     assert np.array_equal(want, complete)
-    for variant, tile_bytes, grid, multicast in [VARIANTS[0], VARIANTS[1], VARIANTS[4], VARIANTS[6], VARIANTS[7], VARIANTS[9], VARIANTS[11], VARIANTS[13]]:
+    for variant, tile_bytes, grid, multicast in [VARIANTS[0], VARIANTS[1], VARIANTS[4], VARIANTS[6], VARIANTS[7], VARIANTS[9], VARIANTS[11], VARIANTS[13], VARIANTS[16]]:
         _say(f"[from-gen {case['name']} variant {variant} tile {tile_bytes} grid {grid} multicast {multicast}]")
         with make_plan(case, B.HF_GATHER_FROM_GEN) as pl:
-            pl.set_param(B.HF_PARAM_TILE_BYTES, tile_bytes)
-            if variant == B.HF_VARIANT_PARTS:
-                pl.set_param(B.HF_PARAM_PART_BYTES, abs(grid))
-                pl.set_param(B.HF_PARAM_WG_THREADS, 64 if grid < 0 else 256)
-            else:
-                pl.set_param(B.HF_PARAM_GRID_WGS, grid)
-            pl.set_param(B.HF_PARAM_VARIANT, variant)
-            pl.set_param(B.HF_PARAM_MULTICAST, multicast)
+            _configure(pl, variant, tile_bytes, grid, multicast)
             ar = Arena(pl)
             ar.train.copy_(torch.from_numpy(train.view(np.int16)))
             ar.gen.fill_(_i16(CANARY))
