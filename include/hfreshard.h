@@ -14,6 +14,11 @@
  * Conventions
  *   - plain C ABI, no exceptions cross it; every function that can fail returns
  *     0 (HF_OK) or a negative hf_status; hf_last_error() gives a thread-local text.
+ *   - threads: queries and the execution entry points take a const plan and may run
+ *     concurrently on one plan from several host threads (each on a stream of its own, on
+ *     buffers the caller keeps apart); hf_plan_set_param, hf_debug_restrict_kinds and
+ *     hf_plan_destroy need the plan for themselves.  hf_reshard_execute_static shares one
+ *     staging array per GPU (see there).
  *   - "device pointer" = memory of the HIP device that was current when the plan
  *     was built; "host pointer" = ordinary process memory.
  *   - sizes and offsets are in BYTES unless a name says otherwise; weights are
