@@ -10,7 +10,7 @@ import pytest
 
 from oracle.reshard_oracle import GenLayout, Model, TrainLayout
 from paper_2409_19256_amd import Plan, binding as B
-from tests.cases import BASELINE, SMALL
+from tests.cases import BASELINE, MEDIUM, SMALL
 from tests.libcases import make_plan, model_dict
 from tests.oracle_util import POISON, make_oracle, mat_ranks, seeded_train_buf, source_index_map
 from tests.plan_interp import run_descs, run_tiles
@@ -485,6 +485,27 @@ def test_default_multicast_mode_follows_the_fan_out():
             pl.validate()
     with make_plan(SMALL[0], HOST) as pl:
         assert B.hf_plan_set_param(pl._h, B.HF_PARAM_MULTICAST, -2) == B.HF_EINVAL
+
+
+def test_queries_from_several_threads_agree():
+    """Queries take a const plan: eight host threads reading one plan at once (ctypes releases
+    the interpreter lock during the calls) see what one thread sees, and errors stay per thread."""
+    from concurrent.futures import ThreadPoolExecutor
+    with make_plan(MEDIUM[0], HOST) as pl:
+        def read(k):
+            if k % 2:
+                assert B.hf_plan_get_desc(pl._h, 0, 1 << 40, C.byref(B.hf_desc())) == B.HF_ERANGE
+                assert b"no such descriptor" in B.hf_last_error()
+            out = [(d.src_off, d.dst_off, d.rows, d.row_bytes) for d in pl.descs(0)]
+            pl.validate()
+            if not k % 2:
+                assert B.hf_plan_rank_coords(pl._h, -1, (C.c_int32 * 6)()) == B.HF_ERANGE
+                assert b"rank out of range" in B.hf_last_error()
+            return out
+        ref = read(0)
+        with ThreadPoolExecutor(8) as pool:
+            for got in pool.map(read, range(8)):
+                assert got == ref
 
 
 def test_check_buffers_on_the_host():
