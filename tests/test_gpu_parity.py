@@ -209,6 +209,47 @@ def test_subset_of_materialised_ranks_and_stream():
                     assert (back[s] == 0xBEEF).all()
 
 
+def test_one_plan_two_host_threads_two_streams():
+    """The execution entry points take a const plan: two host threads run the same plan at the
+    same time, each on a stream and on buffers of its own (streams of default priority), and
+    both sets of generation buffers equal the oracle after every round."""
+    import threading
+    case = MEDIUM[0]
+    orc = make_oracle(case)
+    ranks = list(range(orc.n_ranks))
+    trains = [seeded_train_buf(orc, 31), seeded_train_buf(orc, 32)]
+    wants = [orc.reshard(t, np.full(orc.gen_region_offsets(ranks)[-1], CANARY, np.uint16), ranks) for t in trains]
+    with make_plan(case, B.HF_COPY_OWN) as pl:
+        arenas = [Arena(pl), Arena(pl)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for ar, t in zip(arenas, trains):
+            ar.train.copy_(torch.from_numpy(t.view(np.int16)))
+        torch.cuda.synchronize()
+        errors = []
+
+        def work(k):
+            try:
+                for _ in range(20):
+                    with torch.cuda.stream(streams[k]):
+                        arenas[k].gen.fill_(_i16(CANARY))
+                        pl.execute(arenas[k].train_ptr, arenas[k].gen_ptr, streams[k].cuda_stream)
+                        pl.back(arenas[k].train_ptr, arenas[k].gen_ptr, streams[k].cuda_stream)
+                    streams[k].synchronize()
+                    if not np.array_equal(_d2h(arenas[k].gen), wants[k]) or not np.array_equal(_d2h(arenas[k].train), trains[k]):
+                        errors.append(k)
+                        return
+            except Exception as e:                                  # noqa: BLE001 - reported by the main thread
+                errors.append(repr(e))
+
+        threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join(timeout=100)
+        assert not any(t.is_alive() for t in threads)
+        assert errors == []
+
+
 def test_vanilla_grouping_on_gpu():
     from oracle.reshard_oracle import GenLayout
     case = dict(MEDIUM[1], gen=GenLayout(1, 2, "vanilla"), name="mid_vanilla")
