@@ -191,7 +191,7 @@ def main():
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--grid", type=int, default=None)
-    ap.add_argument("--multicast", type=int, default=None, choices=[0, 1, 2])
+    ap.add_argument("--multicast", type=int, default=None, choices=[0, 1, 2, 3])
     ap.add_argument("--part-bytes", type=int, default=None)
     ap.add_argument("--mc-block-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -317,6 +317,8 @@ def main():
                    "bytes_written": W, "unique_bytes_read": R, "arena_bytes": ar.buf.numel() * 2,
                    "tile_bytes": plan.get_param(B.HF_PARAM_TILE_BYTES), "grid_wgs": plan.get_param(B.HF_PARAM_GRID_WGS),
                    "part_bytes": plan.get_param(B.HF_PARAM_PART_BYTES), "mc_block_bytes": plan.get_param(B.HF_PARAM_MC_BLOCK_BYTES),
+                   "prefetch_block_bytes": plan.get_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES),
+                   "prefetch_merge": plan.get_param(B.HF_PARAM_PREFETCH_MERGE),
                    "variant": plan.get_param(B.HF_PARAM_VARIANT), "multicast": int(multicast),
                    "unicast_equivalent_GBps": round(2 * W / (avg_kernel_ms * 1e-3) / 1e9, 1),
                    "tiles": plan.num_tiles(direction),

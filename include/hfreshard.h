@@ -167,11 +167,19 @@ typedef struct {
   uint32_t n_dst;        /* Multicast: the source tile is read once and written to
                             n_dst destinations with the same row stride (one training
                             piece wanted by several ranks of a micro-DP group).  0 = a
-                            prefetch tile: loaded and stored nowhere (dst_off unused)    */
-  uint32_t dst_list;     /* position of destinations 2..n_dst in the plan's list of extra
-                            destination offsets (see hf_plan_get_tile_dst)               */
+                            load-only tile: loaded and stored nowhere (dst_off unused)   */
+  uint32_t dst_list;     /* n_dst > 1: position of destinations 2..n_dst in the plan's list
+                            of extra destination offsets (see hf_plan_get_tile_dst).
+                            n_dst == 0: 0 = the rows are loaded like those of a copy tile;
+                            c > 0 (= rows, at most HF_MAX_PREFETCH_CHUNKS) = chunked form:
+                            the rows are c source chunks that c later copy tiles read, and
+                            the workgroup with part number k loads part k of EVERY chunk
+                            (the bytes the workgroups with part number k of those copy
+                            tiles will want; same workgroup index mod 8 = same XCD)      */
   uint32_t _pad;
 } hf_tile;
+
+#define HF_MAX_PREFETCH_CHUNKS 8
 
 #define HF_DIR_TRAIN_TO_GEN 0
 #define HF_DIR_GEN_TO_TRAIN 1
@@ -312,8 +320,8 @@ HF_API int hf_calib_fanout(const void *src, void *dst, size_t bytes, int n_dst, 
                     size_t block_bytes, int wg_bytes, void *hip_stream);
 
 /* ---- tuning (host; takes effect on the next launch) -----------------------------
- * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_PREFETCH_BLOCK_BYTES and
- * HF_PARAM_ROW_INTERLEAVE re-tile and re-upload; HF_PARAM_MULTICAST uploads the work list of
+ * HF_PARAM_TILE_BYTES, HF_PARAM_MC_BLOCK_BYTES, HF_PARAM_PREFETCH_BLOCK_BYTES, HF_PARAM_PREFETCH_MERGE
+ * and HF_PARAM_ROW_INTERLEAVE re-tile and re-upload; HF_PARAM_MULTICAST uploads the work list of
  * the new mode and frees the old one (they allocate; not for the hot path).  Only the work lists of the current mode are resident on the device. */
 enum {
   HF_PARAM_TILE_BYTES = 0,   /* bytes of work per tile, 4096 .. 4 MiB, multiple of 4096   */
@@ -324,8 +332,8 @@ enum {
                                 every mode; the modes differ in HBM reads and in speed.
                                 Default (and HF_MULTICAST_AUTO): chosen from the fan-out of
                                 the list, i.e. bytes written per distinct byte read, as
-                                measured: about 2 -> REGISTERS, 3 -> CACHE_BLOCKED, 4 and
-                                more -> PREFETCHED (re-chosen when the list is rebuilt;
+                                measured: about 2 -> REGISTERS, 3 and more -> PREFETCHED
+                                (re-chosen when the list is rebuilt;
                                 hf_plan_get_param returns the mode in force).  When no piece
                                 of the plan has more than one destination (e.g. only one
                                 rank per micro-DP group is materialised) every mode runs
@@ -355,6 +363,11 @@ enum {
   HF_PARAM_PREFETCH_BLOCK_BYTES = 12, /* HF_MULTICAST_PREFETCHED: source bytes per block, 1 MiB ..
                                 64 MiB, default 8 MiB: the eight 4 MiB L2s must hold a block
                                 until its copies are done (re-tiles and re-uploads)        */
+  HF_PARAM_PREFETCH_MERGE = 13, /* HF_MULTICAST_PREFETCHED: up to this many copy tiles that follow
+                                one another in the source share one chunked load-only tile, whose
+                                wavefronts then have that many loads in flight; 1 ..
+                                HF_MAX_PREFETCH_CHUNKS, or 0 (default) = the library's choice
+                                (2, as measured) (re-tiles and re-uploads)                 */
   HF_PARAM_ROW_INTERLEAVE = 11, /* 1 (default): the tiles of the column stripes that several
                                 training ranks contribute to one row-parallel generation
                                 tensor (o, down) go out round-robin, so that a destination

@@ -37,6 +37,8 @@ HF_BUF_TRAIN, HF_BUF_GEN = 0, 1
 (HF_PARAM_TILE_BYTES, HF_PARAM_GRID_WGS, HF_PARAM_VARIANT, HF_PARAM_MULTICAST, HF_PARAM_CACHE_POLICY, HF_PARAM_PART_BYTES,
  HF_PARAM_MC_BLOCK_BYTES) = range(7)
 HF_PARAM_MAX_WGS_PER_LAUNCH, HF_PARAM_WG_THREADS, HF_PARAM_OFFLOAD_WGS, HF_PARAM_ROW_INTERLEAVE, HF_PARAM_PREFETCH_BLOCK_BYTES = 8, 9, 10, 11, 12
+HF_PARAM_PREFETCH_MERGE = 13
+HF_MAX_PREFETCH_CHUNKS = 8
 HF_MULTICAST_AUTO = -1
 HF_MULTICAST_OFF, HF_MULTICAST_REGISTERS, HF_MULTICAST_CACHE_BLOCKED, HF_MULTICAST_PREFETCHED = 0, 1, 2, 3
 HF_STATIC_SCRATCH_BYTES = 16 << 20

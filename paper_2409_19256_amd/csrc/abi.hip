@@ -431,6 +431,10 @@ int hf_plan_set_param(hf_plan *plan, int param, int64_t value) {
     if (value < (1 << 20) || value > (64 << 20)) return fail(HF_EINVAL, "prefetch block must be in [1 MiB, 64 MiB]");
     p.prefetch_block_bytes = value;
     return retile(p, p.tile_bytes);
+  case HF_PARAM_PREFETCH_MERGE:
+    if (value < 0 || value > HF_MAX_PREFETCH_CHUNKS) return fail(HF_EINVAL, "prefetch merge must be in [0, 8]");
+    p.prefetch_merge = value;
+    return retile(p, p.tile_bytes);
   case HF_PARAM_ROW_INTERLEAVE:
     if (value != 0 && value != 1) return fail(HF_EINVAL, "row interleave must be 0 or 1");
     p.row_interleave = value;
@@ -479,6 +483,7 @@ int64_t hf_plan_get_param(const hf_plan *plan, int param) {
   case HF_PARAM_OFFLOAD_WGS: return plan->p.offload_wgs;
   case HF_PARAM_ROW_INTERLEAVE: return plan->p.row_interleave;
   case HF_PARAM_PREFETCH_BLOCK_BYTES: return plan->p.prefetch_block_bytes;
+  case HF_PARAM_PREFETCH_MERGE: return plan->p.effective_prefetch_merge();
   case HF_PARAM_WG_THREADS: return plan->p.wg_threads;
   case HF_PARAM_MAX_WGS_PER_LAUNCH: return plan->p.max_wgs_per_launch;
   case HF_PARAM_CACHE_POLICY: return plan->p.cache_policy;

@@ -89,7 +89,7 @@ int main(int argc, char **argv) {
   };
   int config = 2, steps = 10, warmup = 3, back = 0, install = 0, graph = 0, offload = 0;
   long long multicast = -1, variant = -1, tile_bytes = 0, part_bytes = 0, mc_block = 0, grid = 0, policy = -2, calib = 0, kind_mask = 0,
-            wg_threads = 0, resp_tokens = 0, ceilings = 0, offload_wgs = 0, row_interleave = -1, pf_block = 0;
+            wg_threads = 0, resp_tokens = 0, ceilings = 0, offload_wgs = 0, row_interleave = -1, pf_block = 0, pf_merge = 0;
   unsigned flags = HF_SKIP_OWN;
   std::vector<int32_t> mat_override, train_override, gen_override;
   auto int_list = [](const std::string &list) {
@@ -130,6 +130,7 @@ int main(int argc, char **argv) {
     else if (a == "--offload-wgs") offload_wgs = val();
     else if (a == "--row-interleave") row_interleave = val();
     else if (a == "--prefetch-block-bytes") pf_block = val();
+    else if (a == "--prefetch-merge") pf_merge = val();
     else if (a == "--mat") mat_override = int_list(i + 1 < argc ? argv[++i] : "");     // ranks to materialise instead of the configuration's
     else if (a == "--train") train_override = int_list(i + 1 < argc ? argv[++i] : ""); // p,t,d instead of the configuration's
     else if (a == "--gen") gen_override = int_list(i + 1 < argc ? argv[++i] : "");     // p_g,t_g instead of the configuration's
@@ -137,7 +138,7 @@ int main(int argc, char **argv) {
       std::fprintf(stderr, "usage: hfbench [--config 1..5] [--steps K] [--warmup W] [--back | --install-own] [--copy-own] [--vanilla] [--from-gen] "
                            "[--multicast 0|1|2|3] [--variant V] [--tile-bytes B] [--part-bytes B] [--mc-block-bytes B] [--grid G] "
                            "[--cache-policy P] [--calib-copy-bytes B] [--kind-mask M] [--wg-threads 64|256] [--mat r0,r1,..] [--train p,t,d] [--gen pg,tg] "
-                           "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]] [--row-interleave 0|1] [--prefetch-block-bytes B]\n");
+                           "[--responses TOKENS_PER_REPLICA] [--ceilings SOURCE_BYTES] [--graph] [--offload [--offload-wgs G]] [--row-interleave 0|1] [--prefetch-block-bytes B] [--prefetch-merge 1..8]\n");
       return 2;
     }
   }
@@ -173,6 +174,7 @@ int main(int argc, char **argv) {
   if (wg_threads) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_WG_THREADS, wg_threads));
   if (offload_wgs) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_OFFLOAD_WGS, offload_wgs));
   if (pf_block) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_PREFETCH_BLOCK_BYTES, pf_block));
+  if (pf_merge) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_PREFETCH_MERGE, pf_merge));
   if (row_interleave >= 0) HF_CHECK(hf_plan_set_param(plan, HF_PARAM_ROW_INTERLEAVE, row_interleave));
 
   const size_t tb = hf_plan_train_bytes(plan), gb = hf_plan_gen_bytes(plan);

@@ -74,6 +74,7 @@ struct Plan {
   bool has_sharing = false; // some training piece has more than one destination
   // multicast mode that execute really uses: without sharing the multicast lists are the
   // one-destination work in another order, and the plain list with streaming loads is faster
+  int64_t effective_prefetch_merge() const;
   int64_t effective_multicast() const { return has_sharing ? multicast : (int64_t)HF_MULTICAST_OFF; }
   // host copy of the work list hf_reshard_execute runs in the current mode, and its length
   const std::vector<hf_tile> &active_fwd() const {
@@ -98,6 +99,7 @@ struct Plan {
   bool multicast_auto = true; // the mode follows the list's fan-out until the caller names one
   int64_t mc_block_bytes = 2 << 20;
   int64_t prefetch_block_bytes = 8 << 20;
+  int64_t prefetch_merge = 0; // copy tiles per chunked load-only tile; 0 = chosen from the fan-out
   int64_t cache_policy = -1; // auto
   int64_t part_bytes = 0; // 0 = chosen per launch
   int64_t max_wgs_per_launch = 0xFFFFFFFFll / 256; // a grid holds fewer than 2^32 threads
@@ -136,6 +138,8 @@ int build_plan(const hf_model_desc &m, const hf_train_layout &tl, const hf_gen_l
 // (Re)creates the tile lists from the descriptors with out.tile_bytes.
 int build_tiles(Plan &pl, std::string &err);
 int64_t default_multicast(const Plan &pl); // needs the byte totals build_tiles sets
+int64_t default_prefetch_merge(const Plan &pl); // likewise
+inline int64_t Plan::effective_prefetch_merge() const { return prefetch_merge ? prefetch_merge : default_prefetch_merge(*this); }
 // Host-side consistency check (see hf_plan_validate).
 int validate_plan(const Plan &pl, std::string &err);
 uint64_t desc_bytes(const hf_desc &d);

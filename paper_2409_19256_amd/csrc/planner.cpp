@@ -452,19 +452,25 @@ void tile_desc(std::vector<hf_tile> &out, const hf_desc &d, uint64_t tile_bytes)
 } // namespace
 
 // Multicast mode when the caller leaves the choice to the library, from the list's fan-out
-// (bytes written per distinct byte read).  Measured on the Llama-7B and 13B shapes under
-// training TP 8 with generation TP 1, 2, 4, own pieces in the list or not, in several
-// processes on several machines:
-//   2 destinations per piece: registers 3-5 % ahead of cache-blocked, prefetched 15 % behind;
-//   3: cache-blocked and registers level on average, registers varying by 10 % from process
-//      to process, prefetched 4 % behind;
-//   4: prefetched level with or ahead of the others and the steadiest;
+// (bytes written per distinct byte read).  Measured on the Llama-7B, 13B and 34B shapes under
+// training TP 8 (and TP 4 x PP 2) with generation TP 1, 2, 4, own pieces in the list or not, in
+// several processes on several machines:
+//   2 destinations per piece: registers and prefetched level, cache-blocked 3-5 % behind;
+//   3: prefetched 1-3 % ahead of cache-blocked on average and never behind it; registers
+//      between 3 % ahead and 10 % behind from process to process;
+//   4: prefetched 3-8 % ahead of the others;
 //   7 and 8: prefetched and registers level, cache-blocked 10-13 % behind.
 int64_t default_multicast(const Plan &pl) {
-  if (!pl.unique_bytes[0]) return HF_MULTICAST_CACHE_BLOCKED;
+  if (!pl.unique_bytes[0]) return HF_MULTICAST_PREFETCHED;
   const double fan = (double)pl.moved_bytes[0] / (double)pl.unique_bytes[0];
-  return fan < 2.5 ? HF_MULTICAST_REGISTERS : fan < 3.5 ? HF_MULTICAST_CACHE_BLOCKED : HF_MULTICAST_PREFETCHED;
+  return fan < 2.5 ? HF_MULTICAST_REGISTERS : HF_MULTICAST_PREFETCHED;
 }
+
+// Copy tiles per chunked load-only tile of the prefetched list when the caller leaves it to
+// the library.  Measured on the same workloads: two chunks against one gain 7 % at 3
+// destinations per piece (Llama-7B TP8->TP2: 8.29 against 8.88 ms), 3 % at 4, nothing at 7
+// and 8; four and eight chunks lose the gain again at 3 and 4 and are level at 7 and 8.
+int64_t default_prefetch_merge(const Plan &) { return 2; }
 
 int build_tiles(Plan &pl, std::string &err) {
   if (pl.tile_bytes < 4096 || pl.tile_bytes > (4 << 20) || pl.tile_bytes % 4096) {
@@ -636,21 +642,53 @@ int build_tiles(Plan &pl, std::string &err) {
     flush();
   }
   // prefetched multicast order: the multicast tiles in blocks of at most prefetch_block_bytes of
-  // source; in front of every block a copy of its shared tiles with no destination.  The
-  // workgroup that prefetches a part and the one that copies it have indices a whole number of
-  // tiles apart (a multiple of 8 workgroups), i.e. they run on the same XCD and share its L2.
+  // source; in front of every block the load-only tiles (n_dst == 0) that bring its shared
+  // source bytes into L2.  A shared tile whose source is one contiguous run takes part in a
+  // chunked load-only tile (dst_list = number of chunks): up to prefetch_merge tiles of the
+  // block that follow one another in the source and have the same size share one, and the
+  // group with part number k of that tile loads part k of every chunk.  A shared tile with a
+  // strided source gets a load-only copy of itself.  Every tile, load-only or not, takes the
+  // same number of workgroups (a multiple of 8), so the group that loads part k of a chunk and
+  // the group that copies part k of it run on the same XCD and share its L2.
   pl.tiles_fwd_pf.clear();
   {
     std::vector<const hf_tile *> batch;
     uint64_t batch_bytes = 0;
+    const uint32_t merge = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(pl.effective_prefetch_merge(), HF_MAX_PREFETCH_CHUNKS));
+    std::map<uint64_t, size_t> open; // source offset a chain would continue at -> its load-only tile
     auto flush = [&]() {
-      for (const hf_tile *t : batch)
-        if (t->n_dst > 1) { // a piece with one destination is read once anyway
+      open.clear();
+      for (const hf_tile *t : batch) {
+        if (t->n_dst <= 1) continue; // a piece with one destination is read once anyway
+        const uint64_t payload = (uint64_t)t->rows * t->row_bytes;
+        const bool flat = t->rows == 1 || t->src_row_stride == t->row_bytes;
+        if (!flat || t->src_off % 16 || payload % 16) {
           hf_tile pre = *t;
           pre.n_dst = 0;
           pre.dst_list = 0;
           pl.tiles_fwd_pf.push_back(pre);
+          continue;
         }
+        auto it = open.find(t->src_off);
+        if (it != open.end() && pl.tiles_fwd_pf[it->second].row_bytes == payload) {
+          const size_t at = it->second;
+          hf_tile &pre = pl.tiles_fwd_pf[at];
+          pre.rows = ++pre.dst_list;
+          open.erase(it);
+          if (pre.dst_list < merge) open[t->src_off + payload] = at;
+          continue;
+        }
+        hf_tile pre;
+        std::memset(&pre, 0, sizeof pre);
+        pre.src_off = t->src_off;
+        pre.rows = 1;
+        pre.row_bytes = (uint32_t)payload;
+        pre.src_row_stride = pre.dst_row_stride = (uint32_t)payload;
+        pre.vec_bytes = 16;
+        pre.dst_list = 1;
+        if (merge > 1) open[t->src_off + payload] = pl.tiles_fwd_pf.size();
+        pl.tiles_fwd_pf.push_back(pre);
+      }
       for (const hf_tile *t : batch) pl.tiles_fwd_pf.push_back(*t);
       batch.clear();
       batch_bytes = 0;
@@ -806,20 +844,48 @@ int validate_plan(const Plan &pl, std::string &err) {
   }
   if (!normalise(cb, err, "cache-blocked tiles")) return HF_ERANGE;
   if (!same(cb, mc)) { err = "cache-blocked tiles differ from descriptors"; return HF_ERANGE; }
-  // the prefetched list without its prefetch tiles is the multicast list, and every prefetch tile
-  // names the source of a tile of its block
+  // the prefetched list without its load-only tiles is the multicast list, and in every block
+  // the load-only tiles read exactly the source bytes of the block's shared tiles
   {
     size_t k = 0;
-    std::vector<const hf_tile *> pending;
+    typedef std::pair<uint64_t, uint64_t> Run; // source offset, length
+    std::vector<Run> pre, shared;
+    auto tidy = [](std::vector<Run> &v) {
+      std::sort(v.begin(), v.end());
+      std::vector<Run> m;
+      for (const Run &r : v) {
+        if (!m.empty() && m.back().first + m.back().second == r.first) m.back().second += r.second;
+        else m.push_back(r);
+      }
+      v.swap(m);
+    };
+    auto close_block = [&]() {
+      tidy(pre);
+      tidy(shared);
+      const bool ok = pre == shared;
+      pre.clear();
+      shared.clear();
+      return ok;
+    };
+    bool copying = false;
     for (const hf_tile &t : pl.tiles_fwd_pf) {
-      if (t.n_dst == 0) { pending.push_back(&t); continue; }
+      if (t.n_dst == 0) {
+        if (copying && !close_block()) { err = "prefetched list: load-only tiles do not cover the shared tiles of their block"; return HF_ERANGE; }
+        copying = false;
+        if (t.dst_list > HF_MAX_PREFETCH_CHUNKS || (t.dst_list && (t.rows != t.dst_list || t.src_off % 16 || t.row_bytes % 16 || t.vec_bytes != 16))) {
+          err = "prefetched list: malformed chunked load-only tile";
+          return HF_ERANGE;
+        }
+        for (uint32_t r = 0; r < t.rows; ++r) pre.push_back({t.src_off + (uint64_t)r * t.src_row_stride, t.row_bytes});
+        continue;
+      }
+      copying = true;
       if (k >= pl.tiles_fwd_mc.size() || std::memcmp(&t, &pl.tiles_fwd_mc[k], sizeof t) != 0) { err = "prefetched list differs from the multicast list"; return HF_ERANGE; }
       ++k;
-      if (!pending.empty() && pending.front()->src_off == t.src_off && pending.front()->rows == t.rows &&
-          pending.front()->row_bytes == t.row_bytes && pending.front()->src_row_stride == t.src_row_stride && pending.front()->vec_bytes == t.vec_bytes)
-        pending.erase(pending.begin());
+      if (t.n_dst > 1)
+        for (uint32_t r = 0; r < t.rows; ++r) shared.push_back({t.src_off + (uint64_t)r * t.src_row_stride, t.row_bytes});
     }
-    if (k != pl.tiles_fwd_mc.size() || !pending.empty()) { err = "prefetched list: a prefetch tile has no copy tile"; return HF_ERANGE; }
+    if (k != pl.tiles_fwd_mc.size() || !close_block()) { err = "prefetched list: load-only tiles do not cover the shared tiles of their block"; return HF_ERANGE; }
   }
   // (3b) gathering out of the generation buffers: every source lies inside an own piece of
   // its rank (resident, and never a destination of the same launch)

@@ -185,6 +185,31 @@ __global__ __launch_bounds__(kWG) void reshard_one_tile(const hf_tile *__restric
 // name, so that a profiler's per-kernel statistics keep apart what one process launches
 // over different lists (0 = train->gen without own pieces, 1 = train->gen with own
 // pieces, 2 = any other list: reverse, own pieces alone).
+// A prefetch tile that stands for several copy tiles (n_dst == 0, dst_list = number of chunks):
+// `dst_list` chunks of row_bytes bytes, src_row_stride apart; the group that has part number
+// `part` loads part `part` of EVERY chunk (all loads in flight together).  The copy tiles of
+// the chunks follow later in the list with the same number of workgroups each, so that the
+// workgroup that copies part k of a chunk runs on the XCD (workgroup index mod 8) whose L2
+// this group filled.
+template <int kGroup, int kUnroll>
+__device__ __forceinline__ void prefetch_chunks(const hf_tile &tl, const char *__restrict__ src_base, uint32_t lane, uint32_t part) {
+  constexpr uint32_t kMaxChunks = HF_MAX_PREFETCH_CHUNKS;
+  const uint32_t n = tl.dst_list, bytes = tl.row_bytes, stride = tl.src_row_stride;
+  const char *__restrict__ src = src_base + tl.src_off;
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) {
+    const uint32_t off = ((part * kUnroll + k) * kGroup + lane) * 16u;
+    if (off >= bytes) continue;
+    u32x4 v[kMaxChunks];
+#pragma unroll
+    for (uint32_t j = 0; j < kMaxChunks; ++j)
+      if (j < n) v[j] = *reinterpret_cast<const u32x4 *>(src + (size_t)j * stride + off);
+#pragma unroll
+    for (uint32_t j = 0; j < kMaxChunks; ++j)
+      if (j < n) keep_alive(v[j]);
+  }
+}
+
 template <int kPolicy, int kUnroll, int kThreads, int kList>
 __global__ __launch_bounds__(kThreads) void reshard_parts(const hf_tile *__restrict__ tiles, uint32_t n_tiles, uint32_t parts,
                                                           const uint64_t *__restrict__ extra_dst,
@@ -192,6 +217,10 @@ __global__ __launch_bounds__(kThreads) void reshard_parts(const hf_tile *__restr
   const uint32_t t = blockIdx.x / parts, part = blockIdx.x - t * parts;
   if (t < n_tiles) {
     const hf_tile tl = tiles[t];
+    if (tl.n_dst == 0 && tl.dst_list != 0) { // uniform
+      prefetch_chunks<kThreads, kUnroll>(tl, src, threadIdx.x, part);
+      return;
+    }
     run_tile<kThreads, kPolicy, kUnroll>(tl, extra_dst, src, dst, threadIdx.x, part, kUnroll * kThreads * 16);
   }
 }

@@ -17,8 +17,9 @@ def run_tiles(tiles, src_u8: np.ndarray, dst_u8: np.ndarray) -> None:
     """tiles: [(hf_tile, [destination offsets])] as Plan.tiles() returns them."""
     for tl, dsts in tiles:
         assert len(dsts) == tl.n_dst
-        if tl.n_dst == 0:          # a prefetch tile: read, written nowhere; the source must exist
+        if tl.n_dst == 0:          # a load-only tile: read, written nowhere; the source must exist
             assert tl.src_off + (tl.rows - 1) * tl.src_row_stride + tl.row_bytes <= src_u8.shape[0]
+            assert tl.dst_list in (0, tl.rows)                    # plain or chunked form
             continue
         assert dsts[0] == tl.dst_off
         for r in range(tl.rows):

@@ -185,7 +185,7 @@ def test_row_interleave_only_changes_the_order_of_the_work(case):
                 got = np.full(want.shape, POISON, np.uint16)
                 run_tiles(tiles, train.view(np.uint8), got.view(np.uint8))
                 assert np.array_equal(got, want)
-                lists[(ri, mc)] = [key(t) for t in tiles]
+                lists[(ri, mc)] = [key(t) for t in tiles if t[0].n_dst]   # load-only tiles follow the order (validate covers them)
         for mc in (0, 1, 2, 3):
             assert sorted(lists[(0, mc)]) == sorted(lists[(1, mc)])
         if orc.a > 1:
@@ -218,52 +218,87 @@ def test_multicast_tiles_read_every_training_piece_once():
             assert pl.num_tiles(0) == (n - singles) * n_dst + singles
 
 
-def test_prefetched_order_touches_each_block_before_it_is_copied():
+def _runs(segs):
+    """Sorted (offset, length) runs with touching neighbours merged."""
+    out = []
+    for o, n in sorted(segs):
+        if out and out[-1][0] + out[-1][1] == o:
+            out[-1][1] += n
+        else:
+            out.append([o, n])
+    return out
+
+
+@pytest.mark.parametrize("merge", [1, 2, 4, 8])
+def test_prefetched_order_touches_each_block_before_it_is_copied(merge):
     """HF_MULTICAST_PREFETCHED on Llama-7B TP8->TP2: blocks of at most 8 MiB of source; every block
-    starts with one destination-less tile per shared tile, with the same source geometry and in
-    the same order as the copy tiles that follow; a prefetch tile and its copy tile are a whole
-    number of tiles apart (same XCD for every part)."""
+    starts with load-only tiles that read exactly the source bytes of the block's shared copy
+    tiles; a chunked load-only tile stands for at most `merge` copy tiles, its chunks are as long
+    as those tiles and 16-byte aligned (part k of a chunk = part k of its copy tile: same
+    workgroup index mod 8, same XCD)."""
     with make_plan(BASELINE[1], HOST) as pl:
         pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED)
+        assert pl.get_param(B.HF_PARAM_PREFETCH_MERGE) == 2          # the library's choice at three destinations
+        pl.set_param(B.HF_PARAM_PREFETCH_MERGE, merge)
         block = pl.get_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES)
         assert block == 8 << 20
         t = B.hf_tile()
-
-        def tile(i):
-            B.check(B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)), "get_tile")
-            return (t.src_off, t.rows, t.row_bytes, t.src_row_stride, t.vec_bytes), t.n_dst, t.rows * t.row_bytes
-
         n = pl.num_tiles(0)
-        i = blocks = copies = 0
-        while i < min(n, 30000):
-            pre = []
-            while tile(i)[1] == 0:
-                pre.append(tile(i)[0])
+        i = blocks = 0
+        widest = 0
+        while i < min(n, 10000):
+            pre, shared, size, sizes = [], [], 0, set()
+            while B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)) == 0 and t.n_dst == 0:
+                assert t.dst_list == t.rows and 1 <= t.rows <= merge and t.vec_bytes == 16      # flat sources: chunked form
+                assert t.src_off % 16 == 0 and t.row_bytes % 16 == 0 and t.src_row_stride == t.row_bytes
+                widest = max(widest, t.rows)
+                pre += [(t.src_off + r * t.src_row_stride, t.row_bytes) for r in range(t.rows)]
+                sizes.add(t.row_bytes)
                 i += 1
-            assert pre, "a block starts with its prefetch tiles"
-            shared, size = [], 0
-            while i < n and tile(i)[1] != 0:
-                geo, n_dst, nbytes = tile(i)
-                if n_dst > 1:
-                    shared.append(geo)
-                size += nbytes
-                copies += 1
+            assert pre, "a block starts with its load-only tiles"
+            while i < n and B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)) == 0 and t.n_dst != 0:
+                if t.n_dst > 1:
+                    shared += [(t.src_off + r * t.src_row_stride, t.row_bytes) for r in range(t.rows)]
+                    assert t.rows * t.row_bytes in sizes              # a chunk is as long as its copy tile
+                size += t.rows * t.row_bytes
                 i += 1
-            assert shared == pre and size <= block
+            assert _runs(pre) == _runs(shared) and size <= block
             blocks += 1
-        assert blocks > 5
+        assert blocks > 5 and widest == merge
+        pl.validate()
         pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)
         assert pl.num_tiles(0) < n
         with pytest.raises(B.HfError):
             pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, 4096)
+        with pytest.raises(B.HfError):
+            pl.set_param(B.HF_PARAM_PREFETCH_MERGE, 9)
+
+
+def test_prefetched_order_with_strided_sources_keeps_plain_load_only_tiles():
+    """Gathering out of the generation buffers makes the sources of the row-parallel pieces
+    strided: those get a load-only copy of themselves (dst_list 0), the flat ones the chunked form."""
+    with make_plan(MEDIUM[0], HOST | B.HF_GATHER_FROM_GEN) as pl:
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED)
+        pl.set_param(B.HF_PARAM_PREFETCH_MERGE, 4)
+        pl.validate()
+        t = B.hf_tile()
+        forms = set()
+        for i in range(pl.num_tiles(0)):
+            B.check(B.hf_plan_get_tile(pl._h, 0, i, C.byref(t)), "get_tile")
+            if t.n_dst == 0:
+                forms.add("chunked" if t.dst_list else "plain")
+                if not t.dst_list:
+                    assert t.rows > 1 and t.src_row_stride != t.row_bytes
+        assert forms == {"chunked", "plain"}
 
 
 def test_cache_blocked_order_repeats_each_source_block_per_destination():
-    """Default train->gen work list of Llama-7B TP8->TP2: blocks of at most 16 MiB of source,
+    """Cache-blocked train->gen work list of Llama-7B TP8->TP2: blocks of at most 2 MiB of source,
     each block listed d_g-1 = 3 times in a row with the same sources and different
     destinations, so that passes 2 and 3 can be served by L2."""
     with make_plan(BASELINE[1], HOST) as pl:
-        assert pl.get_param(B.HF_PARAM_MULTICAST) == B.HF_MULTICAST_CACHE_BLOCKED
+        assert pl.get_param(B.HF_PARAM_MULTICAST) == B.HF_MULTICAST_PREFETCHED      # the library's choice at 3 destinations
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED)
         block = pl.get_param(B.HF_PARAM_MC_BLOCK_BYTES)
         n = pl.num_tiles(0)
         t = B.hf_tile()
@@ -462,12 +497,12 @@ def test_gather_from_gen_needs_the_whole_micro_dp_group_and_the_hybridflow_group
 
 
 def test_default_multicast_mode_follows_the_fan_out():
-    """Bytes written per distinct byte read: about 2 -> registers, 3 -> cache-blocked, 4 and more -> prefetched;
+    """Bytes written per distinct byte read: about 2 -> registers, 3 and more -> prefetched;
     a caller's choice sticks until HF_MULTICAST_AUTO hands it back."""
     from oracle.reshard_oracle import GenLayout, Model, TrainLayout
     m = Model(2, 64, 8, 8, 8, 96, 128)
     want = {(4, 0): B.HF_MULTICAST_OFF, (4, B.HF_COPY_OWN): B.HF_MULTICAST_REGISTERS,                 # 1 and 2 destinations
-            (2, 0): B.HF_MULTICAST_CACHE_BLOCKED, (2, B.HF_COPY_OWN): B.HF_MULTICAST_PREFETCHED,      # 3 and 4
+            (2, 0): B.HF_MULTICAST_PREFETCHED, (2, B.HF_COPY_OWN): B.HF_MULTICAST_PREFETCHED,         # 3 and 4
             (1, 0): B.HF_MULTICAST_PREFETCHED, (1, B.HF_COPY_OWN): B.HF_MULTICAST_PREFETCHED}         # 7 and 8
     for (tg, flag), mode in want.items():
         case = dict(name="fan", model=m, train=TrainLayout(1, 8, 1), gen=GenLayout(1, tg))

@@ -19,9 +19,10 @@ def _i16(x):
 
 
 def test_work_list_beyond_the_static_scratch_is_refused():
-    """Size check on the host, before anything touches a device: Llama-13B's default work
-    list (604 k tiles, 29 MB) does not fit 16 MiB; with 512 KiB tiles it does."""
+    """Size check on the host, before anything touches a device: Llama-13B's cache-blocked
+    work list (604 k tiles, 29 MB) does not fit 16 MiB; with 512 KiB tiles it does."""
     with make_plan(BASELINE[2], B.HF_PLAN_HOST_ONLY) as pl:
+        pl.set_param(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED)
         assert pl.num_tiles(0) * 48 > B.HF_STATIC_SCRATCH_BYTES
         assert B.hf_reshard_execute_static(pl._h, 1 << 20, 1 << 40, None) == B.HF_ERANGE
         assert b"static scratch" in B.hf_last_error()
