@@ -12,9 +12,10 @@
 // dispatcher hands out workgroups in index order, so the chip works on one narrow window
 // of source and destination addresses that moves through the list, and a slow CU simply
 // takes fewer workgroups.  One training piece wanted by several ranks of a micro-DP group
-// (Section 5.3) is served either by listing its tiles once per destination in an order
-// that lets L2 serve the re-reads (cache-blocked list, the default) or by tiles that name
-// several destinations (loaded once, stored to each).
+// (Section 5.3) is served by tiles that name several destinations (loaded once, stored to
+// each), by default with load-only tiles in front of every block of the list that bring the
+// block into the L2 of the XCD that will copy it (prefetched list), or by listing its tiles
+// once per destination in an order that lets L2 serve the re-reads (cache-blocked list).
 //
 // Kept beside it, selectable per plan, for measurements: persistent workgroups that stride
 // over the tile list, the same with one wavefront per stride (wavefront-level dispatch),
