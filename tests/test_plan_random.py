@@ -33,7 +33,8 @@ def cases(draw):
     mat = draw(st.one_of(st.none(), st.lists(st.integers(0, n - 1), min_size=1, max_size=min(n, 5), unique=True)))
     flags = draw(st.sampled_from([0, B.HF_COPY_OWN, B.HF_PLAN_OFFLOAD, B.HF_COPY_OWN | B.HF_PLAN_OFFLOAD]))
     params = dict(tile=draw(st.sampled_from([4096, 8192, 131072])), mc=draw(st.sampled_from([0, 1, 2, 3])),
-                  block=draw(st.sampled_from([1 << 20, 2 << 20])), tiles=draw(st.booleans()))
+                  block=draw(st.sampled_from([1 << 20, 2 << 20])), tiles=draw(st.booleans()),
+                  merge=draw(st.sampled_from([0, 1, 2, 3, 8])), row_interleave=draw(st.sampled_from([1, 1, 0])))
     return case, mat, flags, params
 
 
@@ -56,6 +57,9 @@ def test_random_plans_reproduce_oracle(c):
         pl.set_param(B.HF_PARAM_TILE_BYTES, prm["tile"])
         pl.set_param(B.HF_PARAM_MULTICAST, prm["mc"])
         pl.set_param(B.HF_PARAM_MC_BLOCK_BYTES, prm["block"])
+        pl.set_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES, prm["block"])
+        pl.set_param(B.HF_PARAM_PREFETCH_MERGE, prm["merge"])
+        pl.set_param(B.HF_PARAM_ROW_INTERLEAVE, prm["row_interleave"])
         pl.validate()
         got = np.full(want.shape, POISON, np.uint16)
         if prm["tiles"]:
