@@ -511,8 +511,8 @@ def test_llama7b_full_size_every_launch_configuration():
     """Config 2 (the headline workload), whole buffers: the oracle's generation buffers are
     assembled once in device memory (every tensor from the oracle, canaries between them);
     then every launch configuration must reproduce that buffer exactly: bench.py's default
-    (SKIP_OWN, cache-blocked list), multicast off and in registers, the persistent-wavefront
-    kernel, the gather out of the generation buffers (HF_GATHER_FROM_GEN) and the HF_COPY_OWN
+    (SKIP_OWN, prefetched list), multicast off, in registers and cache-blocked, another
+    load-only tile size, the persistent-wavefront kernel, the gather out of the generation buffers (HF_GATHER_FROM_GEN) and the HF_COPY_OWN
     plan (one-launch full refresh)."""
     t0 = time.perf_counter()
     case, cfg_index = BASELINE[1], 1
@@ -536,7 +536,9 @@ def test_llama7b_full_size_every_launch_configuration():
         configs = [("default", []),
                    ("multicast off", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_OFF)]),
                    ("multicast in registers", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_REGISTERS)]),
-                   ("multicast in registers, prefetched", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED)]),
+                   ("cache-blocked list", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED)]),
+                   ("prefetched, four copy tiles per load-only tile", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_PREFETCHED),
+                                                                       (B.HF_PARAM_PREFETCH_MERGE, 4)]),
                    ("persistent wavefronts", [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_CACHE_BLOCKED),
                                               (B.HF_PARAM_VARIANT, B.HF_VARIANT_WAVE_PERSISTENT), (B.HF_PARAM_TILE_BYTES, 16384)])]
         for label, params in configs:
