@@ -472,46 +472,47 @@ int64_t default_multicast(const Plan &pl) {
 // and 8; four and eight chunks lose the gain again at 3 and 4 and are level at 7 and 8.
 int64_t default_prefetch_merge(const Plan &) { return 2; }
 
-int build_tiles(Plan &pl, std::string &err) {
-  if (pl.tile_bytes < 4096 || pl.tile_bytes > (4 << 20) || pl.tile_bytes % 4096) {
-    err = "tile bytes must be a multiple of 4096 in [4096, 4 MiB]";
-    return HF_EINVAL;
+namespace {
+
+bool wanted(const Plan &pl, const hf_desc &d) { return (pl.kind_mask >> d.kind) & 1; }
+
+// one-destination lists in descriptor order, except that a run of row-parallel
+// descriptors into the same destination tensor (its column stripes) is tiled round-robin,
+// for the DRAM-row reason given at the multicast list below
+void tile_list(const Plan &pl, const std::vector<hf_desc> &descs, std::vector<hf_tile> &out) {
+  std::vector<std::vector<hf_tile>> run;
+  for (size_t i = 0; i < descs.size();) {
+    if (!wanted(pl, descs[i])) { ++i; continue; }
+    size_t j = i + 1;
+    if (descs[i].kind == HF_ROW && pl.row_interleave)
+      while (j < descs.size() && descs[j].kind == HF_ROW && descs[j].dst_rank == descs[i].dst_rank &&
+             descs[j].tensor_id == descs[i].tensor_id && descs[j].layer == descs[i].layer)
+        ++j;
+    if (j == i + 1) {
+      tile_desc(out, descs[i], (uint64_t)pl.tile_bytes);
+    } else {
+      run.assign(j - i, {});
+      size_t longest = 0;
+      for (size_t k = i; k < j; ++k) {
+        tile_desc(run[k - i], descs[k], (uint64_t)pl.tile_bytes);
+        longest = std::max(longest, run[k - i].size());
+      }
+      for (size_t t = 0; t < longest; ++t)
+        for (auto &r : run)
+          if (t < r.size()) out.push_back(r[t]);
+    }
+    i = j;
   }
+}
+
+// one-destination lists of all four directions
+void build_plain_lists(Plan &pl) {
   pl.tiles_fwd.clear();
   pl.tiles_back.clear();
-  auto wanted = [&](const hf_desc &d) { return (pl.kind_mask >> d.kind) & 1; };
-  // one-destination lists in descriptor order, except that a run of row-parallel
-  // descriptors into the same destination tensor (its column stripes) is tiled round-robin,
-  // for the DRAM-row reason given at the multicast list below
-  auto tile_list = [&](const std::vector<hf_desc> &descs, std::vector<hf_tile> &out) {
-    std::vector<std::vector<hf_tile>> run;
-    for (size_t i = 0; i < descs.size();) {
-      if (!wanted(descs[i])) { ++i; continue; }
-      size_t j = i + 1;
-      if (descs[i].kind == HF_ROW && pl.row_interleave)
-        while (j < descs.size() && descs[j].kind == HF_ROW && descs[j].dst_rank == descs[i].dst_rank &&
-               descs[j].tensor_id == descs[i].tensor_id && descs[j].layer == descs[i].layer)
-          ++j;
-      if (j == i + 1) {
-        tile_desc(out, descs[i], (uint64_t)pl.tile_bytes);
-      } else {
-        run.assign(j - i, {});
-        size_t longest = 0;
-        for (size_t k = i; k < j; ++k) {
-          tile_desc(run[k - i], descs[k], (uint64_t)pl.tile_bytes);
-          longest = std::max(longest, run[k - i].size());
-        }
-        for (size_t t = 0; t < longest; ++t)
-          for (auto &r : run)
-            if (t < r.size()) out.push_back(r[t]);
-      }
-      i = j;
-    }
-  };
-  tile_list(pl.fwd_peer, pl.tiles_fwd);
+  tile_list(pl, pl.fwd_peer, pl.tiles_fwd);
   pl.n_tiles_fwd_peer = pl.tiles_fwd.size();
-  tile_list(pl.fwd_own, pl.tiles_fwd);
-  tile_list(pl.back, pl.tiles_back);
+  tile_list(pl, pl.fwd_own, pl.tiles_fwd);
+  tile_list(pl, pl.back, pl.tiles_back);
   pl.tiles_offload.clear();
   pl.tiles_reload.clear();
   if (pl.flags & HF_PLAN_OFFLOAD) {
@@ -522,185 +523,202 @@ int build_tiles(Plan &pl, std::string &err) {
       std::swap(t.src_row_stride, t.dst_row_stride);
     }
   }
-  // totals of the descriptors that take part (queried on the hot path of harnesses)
-  {
-    std::vector<const hf_desc *> fwd, back;
-    for (const hf_desc &d : pl.fwd_peer) if (wanted(d)) fwd.push_back(&d);
-    if (pl.flags & HF_COPY_OWN)
-      for (const hf_desc &d : pl.fwd_own) if (wanted(d)) fwd.push_back(&d);
-    for (const hf_desc &d : pl.back) if (wanted(d)) back.push_back(&d);
-    pl.moved_bytes[0] = pl.moved_bytes[1] = 0;
-    for (const hf_desc *d : fwd) pl.moved_bytes[0] += desc_bytes(*d);
-    for (const hf_desc *d : back) pl.moved_bytes[1] += desc_bytes(*d);
-    pl.unique_bytes[0] = unique_src_bytes(fwd);
-    pl.unique_bytes[1] = unique_src_bytes(back);
-  }
+}
 
-  // multicast list over the descriptors execute performs: same source bytes and same
-  // geometry -> one tile with several destinations, in order of first appearance
+// totals of the descriptors that take part (queried on the hot path of harnesses)
+void cache_totals(Plan &pl) {
+  std::vector<const hf_desc *> fwd, back;
+  for (const hf_desc &d : pl.fwd_peer) if (wanted(pl, d)) fwd.push_back(&d);
+  if (pl.flags & HF_COPY_OWN)
+    for (const hf_desc &d : pl.fwd_own) if (wanted(pl, d)) fwd.push_back(&d);
+  for (const hf_desc &d : pl.back) if (wanted(pl, d)) back.push_back(&d);
+  pl.moved_bytes[0] = pl.moved_bytes[1] = 0;
+  for (const hf_desc *d : fwd) pl.moved_bytes[0] += desc_bytes(*d);
+  for (const hf_desc *d : back) pl.moved_bytes[1] += desc_bytes(*d);
+  pl.unique_bytes[0] = unique_src_bytes(fwd);
+  pl.unique_bytes[1] = unique_src_bytes(back);
+}
+
+// multicast list over the descriptors execute performs: same source bytes and same
+// geometry -> one tile with several destinations, in order of first appearance
+int build_multicast_list(Plan &pl, std::string &err) {
   pl.tiles_fwd_mc.clear();
   pl.mc_dst.clear();
-  {
-    std::vector<const hf_desc *> active;
-    for (const hf_desc &d : pl.fwd_peer) if (wanted(d)) active.push_back(&d);
-    if (pl.flags & HF_COPY_OWN)
-      for (const hf_desc &d : pl.fwd_own) if (wanted(d)) active.push_back(&d);
-    typedef std::tuple<uint64_t, uint32_t, uint32_t, uint32_t, uint64_t, uint64_t, uint64_t, uint64_t> Key;
-    std::map<Key, size_t> group_of;
-    std::vector<std::vector<const hf_desc *>> groups;
-    for (const hf_desc *d : active) {
-      const Key k{d->src_off, d->n_blocks, d->rows, d->row_bytes, d->src_block_stride, d->src_row_stride,
-                  d->dst_block_stride, d->dst_row_stride};
-      auto it = group_of.find(k);
-      if (it == group_of.end()) {
-        group_of[k] = groups.size();
-        groups.push_back({d});
-      } else {
-        groups[it->second].push_back(d);
-      }
+  std::vector<const hf_desc *> active;
+  for (const hf_desc &d : pl.fwd_peer) if (wanted(pl, d)) active.push_back(&d);
+  if (pl.flags & HF_COPY_OWN)
+    for (const hf_desc &d : pl.fwd_own) if (wanted(pl, d)) active.push_back(&d);
+  typedef std::tuple<uint64_t, uint32_t, uint32_t, uint32_t, uint64_t, uint64_t, uint64_t, uint64_t> Key;
+  std::map<Key, size_t> group_of;
+  std::vector<std::vector<const hf_desc *>> groups;
+  for (const hf_desc *d : active) {
+    const Key k{d->src_off, d->n_blocks, d->rows, d->row_bytes, d->src_block_stride, d->src_row_stride,
+                d->dst_block_stride, d->dst_row_stride};
+    auto it = group_of.find(k);
+    if (it == group_of.end()) {
+      group_of[k] = groups.size();
+      groups.push_back({d});
+    } else {
+      groups[it->second].push_back(d);
     }
-    pl.has_sharing = false;
-    for (const auto &g : groups) pl.has_sharing = pl.has_sharing || g.size() > 1;
-    // tiles of every group (destinations 2..n already appended to mc_dst)
-    std::vector<std::vector<hf_tile>> group_tiles(groups.size());
-    for (size_t gi = 0; gi < groups.size(); ++gi) {
-      const auto &grp_descs = groups[gi];
-      const hf_desc &d0 = *grp_descs[0];
-      tile_desc(group_tiles[gi], d0, (uint64_t)pl.tile_bytes);
-      for (hf_tile &tl : group_tiles[gi]) {
-        tl.n_dst = (uint32_t)grp_descs.size();
-        tl.dst_list = (uint32_t)pl.mc_dst.size();
-        uint64_t g = tl.vec_bytes; // already covers source, first destination, sizes, strides
-        for (size_t j = 1; j < grp_descs.size(); ++j) {
-          const uint64_t off = tl.dst_off - d0.dst_off + grp_descs[j]->dst_off;
-          pl.mc_dst.push_back(off);
-          g |= off;
-        }
-        tl.vec_bytes = vec_of(g);
+  }
+  pl.has_sharing = false;
+  for (const auto &g : groups) pl.has_sharing = pl.has_sharing || g.size() > 1;
+  // tiles of every group (destinations 2..n already appended to mc_dst)
+  std::vector<std::vector<hf_tile>> group_tiles(groups.size());
+  for (size_t gi = 0; gi < groups.size(); ++gi) {
+    const auto &grp_descs = groups[gi];
+    const hf_desc &d0 = *grp_descs[0];
+    tile_desc(group_tiles[gi], d0, (uint64_t)pl.tile_bytes);
+    for (hf_tile &tl : group_tiles[gi]) {
+      tl.n_dst = (uint32_t)grp_descs.size();
+      tl.dst_list = (uint32_t)pl.mc_dst.size();
+      uint64_t g = tl.vec_bytes; // already covers source, first destination, sizes, strides
+      for (size_t j = 1; j < grp_descs.size(); ++j) {
+        const uint64_t off = tl.dst_off - d0.dst_off + grp_descs[j]->dst_off;
+        pl.mc_dst.push_back(off);
+        g |= off;
       }
+      tl.vec_bytes = vec_of(g);
     }
-    // Row-parallel tensors: the a training pieces of one generation tensor are column
-    // stripes of the same destination rows.  Their tiles are emitted round-robin (rows
-    // 0..R of every piece, then the next rows of every piece, ...) so that each
-    // destination row is completed while it is still open in DRAM, instead of being
-    // visited once per stripe with a fraction of a row each time.
-    typedef std::tuple<int, int, int, int, int> SibKey; // tensor, layer, dp, gpp, gtp of the destination
-    std::map<SibKey, std::vector<size_t>> siblings;
-    for (size_t gi = 0; gi < groups.size(); ++gi) {
-      const hf_desc &d0 = *groups[gi][0];
-      if (d0.kind != HF_ROW || !pl.row_interleave) continue;
+  }
+  // Row-parallel tensors: the a training pieces of one generation tensor are column
+  // stripes of the same destination rows.  Their tiles are emitted round-robin (rows
+  // 0..R of every piece, then the next rows of every piece, ...) so that each
+  // destination row is completed while it is still open in DRAM, instead of being
+  // visited once per stripe with a fraction of a row each time.
+  typedef std::tuple<int, int, int, int, int> SibKey; // tensor, layer, dp, gpp, gtp of the destination
+  std::map<SibKey, std::vector<size_t>> siblings;
+  for (size_t gi = 0; gi < groups.size(); ++gi) {
+    const hf_desc &d0 = *groups[gi][0];
+    if (d0.kind != HF_ROW || !pl.row_interleave) continue;
+    const Coords &c = pl.coords[d0.dst_rank];
+    siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}].push_back(gi);
+  }
+  std::vector<char> emitted(groups.size(), 0);
+  for (size_t gi = 0; gi < groups.size(); ++gi) {
+    if (emitted[gi]) continue;
+    const hf_desc &d0 = *groups[gi][0];
+    std::vector<size_t> set{gi};
+    if (d0.kind == HF_ROW && pl.row_interleave) {
       const Coords &c = pl.coords[d0.dst_rank];
-      siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}].push_back(gi);
+      set = siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}];
     }
-    std::vector<char> emitted(groups.size(), 0);
-    for (size_t gi = 0; gi < groups.size(); ++gi) {
-      if (emitted[gi]) continue;
-      const hf_desc &d0 = *groups[gi][0];
-      std::vector<size_t> set{gi};
-      if (d0.kind == HF_ROW && pl.row_interleave) {
-        const Coords &c = pl.coords[d0.dst_rank];
-        set = siblings[SibKey{d0.tensor_id, d0.layer, c.dp, c.gpp, c.gtp}];
-      }
-      size_t longest = 0;
-      for (size_t g2 : set) { emitted[g2] = 1; longest = std::max(longest, group_tiles[g2].size()); }
-      for (size_t i = 0; i < longest; ++i)
-        for (size_t g2 : set)
-          if (i < group_tiles[g2].size()) pl.tiles_fwd_mc.push_back(group_tiles[g2][i]);
-    }
-    if (pl.mc_dst.size() >= (1ull << 32)) { err = "too many multicast destinations; raise the tile size"; return HF_ERANGE; }
+    size_t longest = 0;
+    for (size_t g2 : set) { emitted[g2] = 1; longest = std::max(longest, group_tiles[g2].size()); }
+    for (size_t i = 0; i < longest; ++i)
+      for (size_t g2 : set)
+        if (i < group_tiles[g2].size()) pl.tiles_fwd_mc.push_back(group_tiles[g2][i]);
   }
+  if (pl.mc_dst.size() >= (1ull << 32)) { err = "too many multicast destinations; raise the tile size"; return HF_ERANGE; }
+  return HF_OK;
+}
 
-  // cache-blocked multicast order: the same work as one-destination tiles, arranged so that
-  // a block of at most mc_block_bytes of source is copied to its first destination, then
-  // the same block to the second, ...: only the first pass reads HBM, the later passes
-  // find the block in L2 (workgroups are handed out in list order, and the workgroup that
-  // copies a given source part runs on the same XCD in every pass because each pass spans
-  // a whole number of tiles with a fixed number of workgroups per tile).
+// cache-blocked multicast order: the same work as one-destination tiles, arranged so that
+// a block of at most mc_block_bytes of source is copied to its first destination, then
+// the same block to the second, ...: only the first pass reads HBM, the later passes
+// find the block in L2 (workgroups are handed out in list order, and the workgroup that
+// copies a given source part runs on the same XCD in every pass because each pass spans
+// a whole number of tiles with a fixed number of workgroups per tile).
+void build_cache_blocked_list(Plan &pl) {
   pl.tiles_fwd_cb.clear();
-  {
-    std::vector<const hf_tile *> batch;
-    uint64_t batch_bytes = 0;
-    auto flush = [&]() {
-      if (batch.empty()) return;
-      for (uint32_t j = 0; j < batch[0]->n_dst; ++j)
-        for (const hf_tile *t : batch) {
-          hf_tile one = *t;
-          one.dst_off = j == 0 ? t->dst_off : pl.mc_dst[t->dst_list + j - 1];
-          one.n_dst = 1;
-          one.dst_list = 0;
-          pl.tiles_fwd_cb.push_back(one);
-        }
-      batch.clear();
-      batch_bytes = 0;
-    };
-    for (const hf_tile &t : pl.tiles_fwd_mc) {
-      const uint64_t payload = (uint64_t)t.rows * t.row_bytes;
-      if (!batch.empty() && (t.n_dst != batch[0]->n_dst || batch_bytes + payload > (uint64_t)pl.mc_block_bytes)) flush();
-      batch.push_back(&t);
-      batch_bytes += payload;
-    }
-    flush();
-  }
-  // prefetched multicast order: the multicast tiles in blocks of at most prefetch_block_bytes of
-  // source; in front of every block the load-only tiles (n_dst == 0) that bring its shared
-  // source bytes into L2.  A shared tile whose source is one contiguous run takes part in a
-  // chunked load-only tile (dst_list = number of chunks): up to prefetch_merge tiles of the
-  // block that follow one another in the source and have the same size share one, and the
-  // group with part number k of that tile loads part k of every chunk.  A shared tile with a
-  // strided source gets a load-only copy of itself.  Every tile, load-only or not, takes the
-  // same number of workgroups (a multiple of 8), so the group that loads part k of a chunk and
-  // the group that copies part k of it run on the same XCD and share its L2.
-  pl.tiles_fwd_pf.clear();
-  {
-    std::vector<const hf_tile *> batch;
-    uint64_t batch_bytes = 0;
-    const uint32_t merge = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(pl.effective_prefetch_merge(), HF_MAX_PREFETCH_CHUNKS));
-    std::map<uint64_t, size_t> open; // source offset a chain would continue at -> its load-only tile
-    auto flush = [&]() {
-      open.clear();
+  std::vector<const hf_tile *> batch;
+  uint64_t batch_bytes = 0;
+  auto flush = [&]() {
+    if (batch.empty()) return;
+    for (uint32_t j = 0; j < batch[0]->n_dst; ++j)
       for (const hf_tile *t : batch) {
-        if (t->n_dst <= 1) continue; // a piece with one destination is read once anyway
-        const uint64_t payload = (uint64_t)t->rows * t->row_bytes;
-        const bool flat = t->rows == 1 || t->src_row_stride == t->row_bytes;
-        if (!flat || t->src_off % 16 || payload % 16) {
-          hf_tile pre = *t;
-          pre.n_dst = 0;
-          pre.dst_list = 0;
-          pl.tiles_fwd_pf.push_back(pre);
-          continue;
-        }
-        auto it = open.find(t->src_off);
-        if (it != open.end() && pl.tiles_fwd_pf[it->second].row_bytes == payload) {
-          const size_t at = it->second;
-          hf_tile &pre = pl.tiles_fwd_pf[at];
-          pre.rows = ++pre.dst_list;
-          open.erase(it);
-          if (pre.dst_list < merge) open[t->src_off + payload] = at;
-          continue;
-        }
-        hf_tile pre;
-        std::memset(&pre, 0, sizeof pre);
-        pre.src_off = t->src_off;
-        pre.rows = 1;
-        pre.row_bytes = (uint32_t)payload;
-        pre.src_row_stride = pre.dst_row_stride = (uint32_t)payload;
-        pre.vec_bytes = 16;
-        pre.dst_list = 1;
-        if (merge > 1) open[t->src_off + payload] = pl.tiles_fwd_pf.size();
-        pl.tiles_fwd_pf.push_back(pre);
+        hf_tile one = *t;
+        one.dst_off = j == 0 ? t->dst_off : pl.mc_dst[t->dst_list + j - 1];
+        one.n_dst = 1;
+        one.dst_list = 0;
+        pl.tiles_fwd_cb.push_back(one);
       }
-      for (const hf_tile *t : batch) pl.tiles_fwd_pf.push_back(*t);
-      batch.clear();
-      batch_bytes = 0;
-    };
-    for (const hf_tile &t : pl.tiles_fwd_mc) {
-      const uint64_t payload = (uint64_t)t.rows * t.row_bytes;
-      if (!batch.empty() && batch_bytes + payload > (uint64_t)pl.prefetch_block_bytes) flush();
-      batch.push_back(&t);
-      batch_bytes += payload;
-    }
-    flush();
+    batch.clear();
+    batch_bytes = 0;
+  };
+  for (const hf_tile &t : pl.tiles_fwd_mc) {
+    const uint64_t payload = (uint64_t)t.rows * t.row_bytes;
+    if (!batch.empty() && (t.n_dst != batch[0]->n_dst || batch_bytes + payload > (uint64_t)pl.mc_block_bytes)) flush();
+    batch.push_back(&t);
+    batch_bytes += payload;
   }
+  flush();
+}
+
+// prefetched multicast order: the multicast tiles in blocks of at most prefetch_block_bytes of
+// source; in front of every block the load-only tiles (n_dst == 0) that bring its shared
+// source bytes into L2.  A shared tile whose source is one contiguous run takes part in a
+// chunked load-only tile (dst_list = number of chunks): up to prefetch_merge tiles of the
+// block that follow one another in the source and have the same size share one, and the
+// group with part number k of that tile loads part k of every chunk.  A shared tile with a
+// strided source gets a load-only copy of itself.  Every tile, load-only or not, takes the
+// same number of workgroups (a multiple of 8), so the group that loads part k of a chunk and
+// the group that copies part k of it run on the same XCD and share its L2.
+void build_prefetched_list(Plan &pl) {
+  pl.tiles_fwd_pf.clear();
+  std::vector<const hf_tile *> batch;
+  uint64_t batch_bytes = 0;
+  const uint32_t merge = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(pl.effective_prefetch_merge(), HF_MAX_PREFETCH_CHUNKS));
+  std::map<uint64_t, size_t> open; // source offset a chain would continue at -> its load-only tile
+  auto flush = [&]() {
+    open.clear();
+    for (const hf_tile *t : batch) {
+      if (t->n_dst <= 1) continue; // a piece with one destination is read once anyway
+      const uint64_t payload = (uint64_t)t->rows * t->row_bytes;
+      const bool flat = t->rows == 1 || t->src_row_stride == t->row_bytes;
+      if (!flat || t->src_off % 16 || payload % 16) {
+        hf_tile pre = *t;
+        pre.n_dst = 0;
+        pre.dst_list = 0;
+        pl.tiles_fwd_pf.push_back(pre);
+        continue;
+      }
+      auto it = open.find(t->src_off);
+      if (it != open.end() && pl.tiles_fwd_pf[it->second].row_bytes == payload) {
+        const size_t at = it->second;
+        hf_tile &pre = pl.tiles_fwd_pf[at];
+        pre.rows = ++pre.dst_list;
+        open.erase(it);
+        if (pre.dst_list < merge) open[t->src_off + payload] = at;
+        continue;
+      }
+      hf_tile pre;
+      std::memset(&pre, 0, sizeof pre);
+      pre.src_off = t->src_off;
+      pre.rows = 1;
+      pre.row_bytes = (uint32_t)payload;
+      pre.src_row_stride = pre.dst_row_stride = (uint32_t)payload;
+      pre.vec_bytes = 16;
+      pre.dst_list = 1;
+      if (merge > 1) open[t->src_off + payload] = pl.tiles_fwd_pf.size();
+      pl.tiles_fwd_pf.push_back(pre);
+    }
+    for (const hf_tile *t : batch) pl.tiles_fwd_pf.push_back(*t);
+    batch.clear();
+    batch_bytes = 0;
+  };
+  for (const hf_tile &t : pl.tiles_fwd_mc) {
+    const uint64_t payload = (uint64_t)t.rows * t.row_bytes;
+    if (!batch.empty() && batch_bytes + payload > (uint64_t)pl.prefetch_block_bytes) flush();
+    batch.push_back(&t);
+    batch_bytes += payload;
+  }
+  flush();
+}
+
+} // namespace
+
+int build_tiles(Plan &pl, std::string &err) {
+  if (pl.tile_bytes < 4096 || pl.tile_bytes > (4 << 20) || pl.tile_bytes % 4096) {
+    err = "tile bytes must be a multiple of 4096 in [4096, 4 MiB]";
+    return HF_EINVAL;
+  }
+  build_plain_lists(pl);
+  cache_totals(pl);
+  if (int rc = build_multicast_list(pl, err)) return rc;
+  build_cache_blocked_list(pl);
+  build_prefetched_list(pl);
   if (pl.multicast_auto) pl.multicast = default_multicast(pl);
   if (pl.tiles_fwd.size() >= (1ull << 31) || pl.tiles_back.size() >= (1ull << 31)) {
     err = "too many tiles; raise the tile size";
