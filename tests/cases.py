@@ -26,6 +26,8 @@ SMALL = [
     dict(name="mha_dp2", model=Model(2, 16, 4, 4, 4, 12, 16), train=TrainLayout(2, 2, 2), gen=GenLayout(1, 1)),
     dict(name="odd_rows", model=Model(1, 6, 2, 2, 3, 10, 8), train=TrainLayout(1, 2, 1), gen=GenLayout(1, 1)),
     dict(name="same_layout", model=Model(2, 32, 4, 2, 8, 24, 64), train=TrainLayout(2, 2, 1), gen=GenLayout(2, 2)),
+    # eight pipeline stages merged into one, TP unchanged (micro-DP 8 from PP alone): the layout of Section 8.4's 70B example
+    dict(name="pp8_merge_tp2", model=Model(8, 16, 4, 2, 4, 12, 16), train=TrainLayout(8, 2, 1), gen=GenLayout(1, 2)),
 ]
 
 # Medium shapes: tens of MB, several 128 KiB tiles per descriptor with ragged tails,
