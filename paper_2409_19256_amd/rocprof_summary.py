@@ -46,12 +46,12 @@ def summarise(d: str, calib_bytes: int = 0) -> str:
         factor = {}
         if calib_bytes:
             for (k, c), v in val.items():
-                if "calib_copy" in k:
+                if "calib_copy" in k and sum(v) > 0:   # a counter that reads 0 for the copy (a stall counter) has no byte scale
                     factor[c] = calib_bytes / (sum(v) / len(v))
                     out.append(f"calibration: calib_copy moved {calib_bytes} bytes each way and read {c} = {sum(v)/len(v):.1f} "
                                f"-> {factor[c]:.2f} bytes per counter unit")
         out.append(f"{'kernel':72s} {'counter':12s} {'calls':>6s} {'avg per dispatch':>18s} {'HBM bytes per dispatch':>24s}")
-        for (k, c), v in sorted(val.items(), key=lambda kv: -sum(kv[1]))[:12]:
+        for (k, c), v in sorted(val.items(), key=lambda kv: -sum(kv[1]))[:16]:
             avg = sum(v) / len(v)
             b = f"{avg * factor[c]:24.0f}" if c in factor else f"{'':24s}"
             out.append(f"{k[:72]:72s} {c:12s} {len(v):6d} {avg:18.1f} {b}")
