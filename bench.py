@@ -335,8 +335,9 @@ def main():
                      "avg_kernel_ms": round(avg_kernel_ms, 4),
                      "measured_ceiling": ceilings,
                      "frac_of_measured_mix_ceiling": round(achieved / ceilings["mix_best"], 4) if ceilings else None,
-                     "run_to_run": "the same launch takes 8.3-9.0 ms (0.76-0.81 of peak) from process to process on one box: the "
-                                   "physical pages behind the buffers decide it (measured; not address translation)"},
+                     "run_to_run": ("the same launch takes 8.3-9.0 ms (0.76-0.81 of peak) from process to process on one box: the "
+                                    "physical pages behind the buffers decide it (measured; not address translation)")
+                     if default_config and args.config == 2 and args.direction == "fwd" else None},
         "transition_full_refresh": full_refresh,
     }
     if not args.no_cpu_baseline:
