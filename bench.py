@@ -175,6 +175,64 @@ def measured_ceilings(ar, n_dst, stream):
     return out
 
 
+def placement_ab(cfg, flags, placements, steps):
+    """The time of one launch depends on the physical pages behind the buffers by several per cent, and a process
+    gets them by lot; comparing two launch configurations in two processes compares two lots.  Here every
+    alternative runs on the same `placements` allocations of the buffers: between two of them the buffers are
+    freed, a little more memory is held back, and they are allocated again."""
+    import torch
+
+    from paper_2409_19256_amd import Plan, binding as B
+    from paper_2409_19256_amd.arena import Arena
+    variants = [("library defaults", []),
+                ("prefetched, one load-only tile per copy tile", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_MERGE, 1)]),
+                ("prefetched, 2 copy tiles per load-only tile", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_MERGE, 2)]),
+                ("prefetched, 4 copy tiles per load-only tile", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_MERGE, 4)]),
+                ("prefetched, blocks of 4 MiB", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 4 << 20)]),
+                ("prefetched, blocks of 16 MiB", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 16 << 20)]),
+                ("tiles of 64 KiB", [(B.HF_PARAM_TILE_BYTES, 65536)]),
+                ("tiles of 256 KiB", [(B.HF_PARAM_TILE_BYTES, 262144)]),
+                ("row interleave off", [(B.HF_PARAM_ROW_INTERLEAVE, 0)]),
+                ("cache-blocked list", [(B.HF_PARAM_MULTICAST, 2)]),
+                ("cache-blocked list, blocks of 4 MiB", [(B.HF_PARAM_MULTICAST, 2), (B.HF_PARAM_MC_BLOCK_BYTES, 4 << 20)]),
+                ("multicast in registers", [(B.HF_PARAM_MULTICAST, 1)]),
+                ("multicast off", [(B.HF_PARAM_MULTICAST, 0)])]
+    defaults = [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_AUTO), (B.HF_PARAM_PREFETCH_MERGE, 0), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 8 << 20),
+                (B.HF_PARAM_TILE_BYTES, 131072), (B.HF_PARAM_ROW_INTERLEAVE, 1), (B.HF_PARAM_MC_BLOCK_BYTES, 2 << 20)]
+
+    def timed(ar):
+        for _ in range(2):
+            ar.execute()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()                                  # Arena launches on torch's current stream
+        for _ in range(steps):
+            ar.execute()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    with Plan(cfg["model"], cfg["train"], cfg["gen"], flags=flags, mat_ranks=cfg["mat"]) as plan:
+        res = {name: [] for name, _ in variants}
+        held, ar = [], None
+        for j in range(placements):
+            del ar
+            torch.cuda.empty_cache()
+            held.append(torch.empty((j + 1) * 37 << 20, dtype=torch.uint8, device="cuda"))   # the next allocation gets other pages
+            ar = Arena(plan)
+            ar.train.fill_(1)
+            ar.gen.fill_(2)
+            for name, params in variants:
+                for k, v in defaults + params:
+                    plan.set_param(k, v)
+                res[name].append(timed(ar))
+        print(f"# {cfg['name']}, {'HF_COPY_OWN' if flags & B.HF_COPY_OWN else 'HF_SKIP_OWN'}: ms per launch (mean of {steps}) on {placements} "
+              f"placements of the buffers, the same for every row")
+        for name, _ in variants:
+            v = res[name]
+            print(f"{name:48s} mean {sum(v) / len(v):7.3f} | " + " ".join(f"{x:7.3f}" for x in v))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +258,9 @@ def main():
     ap.add_argument("--calib-copy-bytes", type=int, default=0,
                     help="after the timed region, launch the library's plain copy kernel once over this many bytes "
                          "(a dispatch of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--placement-ab", type=int, default=0, metavar="N",
+                    help="instead of the benchmark line: time the transition under alternative launch parameters over the SAME N "
+                         "physical placements of the buffers (the buffers are re-allocated N times inside this process), prints a table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU: all simulated ranks live in one HBM allocation and there is no "
@@ -216,6 +277,9 @@ def main():
         print("bench.py: no GPU visible; the reshard library has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = dict(CONFIGS[args.config], index=args.config)
+    if args.placement_ab:
+        placement_ab(cfg, B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN, args.placement_ab, args.steps)
+        return
     default_config = (args.flags == "skip_own" and not args.from_gen and args.grouping == "hybridflow" and args.variant is None and args.tile_bytes is None
                       and args.grid is None and args.multicast is None and not args.part_bytes and not args.mc_block_bytes)
     flags = B.HF_COPY_OWN if args.flags == "copy_own" else B.HF_SKIP_OWN
