@@ -189,6 +189,7 @@ def placement_ab(cfg, flags, placements, steps):
                 ("prefetched, 2 copy tiles per load-only tile", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_MERGE, 2)]),
                 ("prefetched, 4 copy tiles per load-only tile", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_MERGE, 4)]),
                 ("prefetched, blocks of 4 MiB", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 4 << 20)]),
+                ("prefetched, blocks of 8 MiB", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 8 << 20)]),
                 ("prefetched, blocks of 16 MiB", [(B.HF_PARAM_MULTICAST, 3), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 16 << 20)]),
                 ("tiles of 64 KiB", [(B.HF_PARAM_TILE_BYTES, 65536)]),
                 ("tiles of 256 KiB", [(B.HF_PARAM_TILE_BYTES, 262144)]),
@@ -197,7 +198,7 @@ def placement_ab(cfg, flags, placements, steps):
                 ("cache-blocked list, blocks of 4 MiB", [(B.HF_PARAM_MULTICAST, 2), (B.HF_PARAM_MC_BLOCK_BYTES, 4 << 20)]),
                 ("multicast in registers", [(B.HF_PARAM_MULTICAST, 1)]),
                 ("multicast off", [(B.HF_PARAM_MULTICAST, 0)])]
-    defaults = [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_AUTO), (B.HF_PARAM_PREFETCH_MERGE, 0), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 8 << 20),
+    defaults = [(B.HF_PARAM_MULTICAST, B.HF_MULTICAST_AUTO), (B.HF_PARAM_PREFETCH_MERGE, 0), (B.HF_PARAM_PREFETCH_BLOCK_BYTES, 6 << 20),
                 (B.HF_PARAM_TILE_BYTES, 131072), (B.HF_PARAM_ROW_INTERLEAVE, 1), (B.HF_PARAM_MC_BLOCK_BYTES, 2 << 20)]
 
     def timed(ar):

@@ -361,7 +361,7 @@ enum {
                                 automatic: 256 for the cache-blocked train->gen list, 64
                                 (one wavefront) for every other list                     */
   HF_PARAM_PREFETCH_BLOCK_BYTES = 12, /* HF_MULTICAST_PREFETCHED: source bytes per block, 1 MiB ..
-                                64 MiB, default 8 MiB: the eight 4 MiB L2s must hold a block
+                                64 MiB, default 6 MiB: the eight 4 MiB L2s must hold a block
                                 until its copies are done (re-tiles and re-uploads)        */
   HF_PARAM_PREFETCH_MERGE = 13, /* HF_MULTICAST_PREFETCHED: up to this many copy tiles that follow
                                 one another in the source share one chunked load-only tile, whose

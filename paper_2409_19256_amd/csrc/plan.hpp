@@ -98,7 +98,8 @@ struct Plan {
   int64_t multicast = HF_MULTICAST_CACHE_BLOCKED;
   bool multicast_auto = true; // the mode follows the list's fan-out until the caller names one
   int64_t mc_block_bytes = 2 << 20;
-  int64_t prefetch_block_bytes = 8 << 20;
+  int64_t prefetch_block_bytes = 6 << 20; // measured over identical buffer placements: 6 MiB is 0.5-2.6 % ahead of 8 MiB on the 7B and 13B
+                                          // shapes at 3 to 7 destinations per piece and level on the 34B shape; 4 MiB and 10+ MiB are behind
   int64_t prefetch_merge = 0; // copy tiles per chunked load-only tile; 0 = chosen from the fan-out
   int64_t cache_policy = -1; // auto
   int64_t part_bytes = 0; // 0 = chosen per launch

@@ -231,7 +231,7 @@ def _runs(segs):
 
 @pytest.mark.parametrize("merge", [1, 2, 4, 8])
 def test_prefetched_order_touches_each_block_before_it_is_copied(merge):
-    """HF_MULTICAST_PREFETCHED on Llama-7B TP8->TP2: blocks of at most 8 MiB of source; every block
+    """HF_MULTICAST_PREFETCHED on Llama-7B TP8->TP2: blocks of at most 6 MiB of source; every block
     starts with load-only tiles that read exactly the source bytes of the block's shared copy
     tiles; a chunked load-only tile stands for at most `merge` copy tiles, its chunks are as long
     as those tiles and 16-byte aligned (part k of a chunk = part k of its copy tile: same
@@ -241,7 +241,7 @@ def test_prefetched_order_touches_each_block_before_it_is_copied(merge):
         assert pl.get_param(B.HF_PARAM_PREFETCH_MERGE) == 2          # the library's choice at three destinations
         pl.set_param(B.HF_PARAM_PREFETCH_MERGE, merge)
         block = pl.get_param(B.HF_PARAM_PREFETCH_BLOCK_BYTES)
-        assert block == 8 << 20
+        assert block == 6 << 20
         t = B.hf_tile()
         n = pl.num_tiles(0)
         i = blocks = 0
